@@ -1,0 +1,160 @@
+/*
+ * moga.h -- C ABI of the MI355X (gfx950) Mixture-of-Groups Attention library.
+ *
+ * The calls follow the MoGA paper (arXiv 2510.18692): Alg. 1 is
+ *     g = router(X);  Q^,K^,V^,cu_seqlen,max_seqlen,permute_index = permute(Q,K,V,g);
+ *     O^ = varlen_attention(Q^,K^,V^,cu_seqlen);  O = repermute(O^, permute_index)
+ * with the router of Eqs. 2-4 (one linear layer, softmax, top-1) and the output of
+ * Eq. 5 (the attention result of a token is multiplied by its router probability).
+ * The *_bwd calls are the derivative of Eq. 5 with the assignment g held constant.
+ *
+ * Conventions shared by every call
+ *   - Every pointer argument except `stream` is a DEVICE pointer owned by the caller;
+ *     tensors must be 16-byte aligned and must not alias each other.  The library
+ *     allocates nothing, keeps no state between calls, and uses only the caller's
+ *     workspace `ws` (size from moga_workspace_bytes; NULL allowed when that size is 0).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work: they never synchronise the host, and outputs are valid in stream order.
+ *   - Return value is a moga_status.  No exceptions, no abort, no printing.  Arguments are
+ *     validated on the host before anything is launched; N == 0 is a successful no-op.
+ *   - Notation: N tokens (batch 1), d_model router input width, M groups, H heads,
+ *     D head_dim.  Token-order tensors are [N, H, D] row-major; group-contiguous
+ *     ("hat") tensors are head-major [H, N, D], row j of a head being sorted slot j.
+ *   - Supported: M in [1, 256]; N < 2^31; dtype F32 with D in {64, 128} (backward: D = 64)
+ *     and dtype BF16 with D = 128.  Anything else returns MOGA_ERR_UNSUPPORTED.
+ */
+#ifndef MOGA_H_
+#define MOGA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MOGA_MAX_GROUPS 256
+
+typedef enum {
+  MOGA_OK = 0,
+  MOGA_ERR_INVALID_ARG = -1, /* NULL required pointer, negative size, misaligned pointer, bad scale */
+  MOGA_ERR_UNSUPPORTED = -2, /* shape / dtype combination the kernels do not cover */
+  MOGA_ERR_WORKSPACE = -3,   /* ws is NULL or smaller than moga_workspace_bytes says */
+  MOGA_ERR_HIP = -4          /* a kernel launch failed (hipGetLastError) */
+} moga_status;
+
+typedef enum { MOGA_F32 = 0, MOGA_BF16 = 1 } moga_dtype;
+
+typedef enum {
+  MOGA_OP_ROUTE = 0,
+  MOGA_OP_PERMUTE = 1,
+  MOGA_OP_ATTN_FWD = 2,
+  MOGA_OP_ATTN_BWD = 3,
+  MOGA_OP_ROUTE_BWD = 4
+} moga_op;
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char* moga_status_string(int status);
+/* Library version, major*10000 + minor*100 + patch. */
+int moga_version(void);
+
+/* Bytes of device workspace the given call needs for these sizes (0 if none). Host-only. */
+size_t moga_workspace_bytes(int op, int64_t N, int H, int D, int M, int d_model, int dtype);
+
+/*
+ * Router, Eqs. 2-4, plus the gate that Eq. 5 multiplies by.
+ *   logits[i][j] = sum_c x[i][c] * w[j][c] (+ bias[j])      fp32-GEMM semantics
+ *   group[i]     = argmax_j logits[i][j], lowest j on ties   (Eq. 4; softmax is monotone)
+ *   probs[i][j]  = softmax_j(logits[i])                      (Eq. 3)
+ *   gate[i]      = probs[i][group[i]]
+ * x [N, d_model] of x_dtype; w [M, d_model] fp32; bias [M] fp32 or NULL.
+ * Outputs: group [N] int32, gate [N] fp32; probs [N, M] fp32 (NULL to skip; the backward
+ * needs it); logits [N, M] fp32 (NULL to skip).  One group and one gate per token,
+ * shared by all heads (Section 3.2).
+ */
+int moga_route(const void* x, int x_dtype, const float* w, const float* bias_or_null,
+               int64_t N, int d_model, int M,
+               int32_t* group, float* gate, float* probs_or_null, float* logits_or_null,
+               void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * permute of Alg. 1: histogram, exclusive prefix sum, stable counting-sort permutation,
+ * and the gather of Q, K, V into group-contiguous head-major layout.
+ *   counts[g]      = #{i : group[i] == g}                       [M]
+ *   cu_seqlens     = exclusive prefix sum of counts, cu[M] = N   [M + 1]
+ *   max_seqlen     = max_g counts[g]                             [1]
+ *   perm[j]        = token in sorted slot j; keys (group, token index) ascending   [N]
+ *   inv_perm[i]    = slot of token i                             [N]
+ *   qh[h][j][:]    = q[perm[j]][h][:]   (same for k, v)
+ * group ids outside [0, M) are clamped into range.  q, k, v may all be NULL to compute
+ * only the integer outputs (then qh, kh, vh are ignored).  All int32 outputs stay on the device.
+ */
+int moga_permute(const int32_t* group, int64_t N, int M,
+                 const void* q, const void* k, const void* v, int dtype, int H, int D,
+                 int32_t* counts, int32_t* cu_seqlens, int32_t* max_seqlen,
+                 int32_t* perm, int32_t* inv_perm,
+                 void* qh, void* kh, void* vh,
+                 void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Variable-length attention of Alg. 1 step 3: Eq. 1 applied independently inside each
+ * group and head, bidirectional:
+ *   oh[h][j] = softmax_k(softmax_scale * qh[h][j] . kh[h][k]) vh[h][k],  k over j's group
+ *   lse[h][j] = log sum_k exp(softmax_scale * qh[h][j] . kh[h][k])      [H, N] fp32
+ * Groups are the row ranges cu_seqlens[g]..cu_seqlens[g+1] (device, [M + 1]); empty groups
+ * do nothing.  softmax_scale must be finite and > 0.  BF16: bf16 MFMA inputs, fp32
+ * accumulation and softmax statistics; F32: fp32 throughout.
+ */
+int moga_group_attn_fwd(const void* qh, const void* kh, const void* vh, int dtype,
+                        int64_t N, int H, int D, const int32_t* cu_seqlens, int M,
+                        float softmax_scale, void* oh, float* lse,
+                        void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * repermute of Alg. 1 with the gate of Eq. 5:
+ *   o[perm[j]][h][:] = gate[perm[j]] * oh[h][j][:]      (gate NULL: plain scatter)
+ */
+int moga_unpermute(const void* oh, int dtype, const int32_t* perm, const float* gate_or_null,
+                   int64_t N, int H, int D, void* o, void* stream);
+
+/*
+ * Backward of moga_unpermute (derivative of Eq. 5 w.r.t. the attention output and the gate):
+ *   d_oh[h][j][:] = gate[perm[j]] * d_o[perm[j]][h][:]
+ *   d_gate[perm[j]] = sum_{h,c} d_o[perm[j]][h][c] * oh[h][j][c]      [N] fp32
+ */
+int moga_unpermute_bwd(const void* d_o, const void* oh, int dtype, const int32_t* perm,
+                       const float* gate, int64_t N, int H, int D,
+                       void* d_oh, float* d_gate, void* stream);
+
+/*
+ * Backward of moga_group_attn_fwd, per group and head, with P = exp(scale*S - lse):
+ *   delta = rowsum(d_oh * oh);  dV = P^T d_oh;  dP = d_oh V^T;  dS = P * (dP - delta)
+ *   dQ = scale * dS K;  dK = scale * dS^T Q
+ * All tensors [H, N, D] in group-contiguous order; lse from the forward call.
+ */
+int moga_group_attn_bwd(const void* d_oh, const void* qh, const void* kh, const void* vh,
+                        const void* oh, const float* lse, int dtype,
+                        int64_t N, int H, int D, const int32_t* cu_seqlens, int M,
+                        float softmax_scale, void* d_qh, void* d_kh, void* d_vh,
+                        void* ws, size_t ws_bytes, void* stream);
+
+/* Backward of the gather in moga_permute: d_q[perm[j]][h][:] = d_qh[h][j][:] (same for k, v). */
+int moga_permute_bwd(const void* d_qh, const void* d_kh, const void* d_vh, int dtype,
+                     const int32_t* perm, int64_t N, int H, int D,
+                     void* d_q, void* d_k, void* d_v, void* stream);
+
+/*
+ * Backward of the router through the gate (the assignment is a constant):
+ *   dr[i][j] = d_gate[i] * gate[i] * ([j == group[i]] - probs[i][j])
+ *   d_w[j][c] = sum_i dr[i][j] * x[i][c]            [M, d_model] fp32
+ *   d_x[i][c] = sum_j dr[i][j] * w[j][c]            [N, d_model] fp32, NULL to skip
+ */
+int moga_route_bwd(const void* x, int x_dtype, const float* w, const float* probs,
+                   const int32_t* group, const float* gate, const float* d_gate,
+                   int64_t N, int d_model, int M, float* d_w, float* d_x_or_null,
+                   void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOGA_H_ */

@@ -1,0 +1,239 @@
+"""ctypes binding of libmoga.so: argument marshalling only.
+
+Every function has the name and the argument order of its C entry point in
+include/moga.h.  torch is used for device memory (`torch.empty`, `.data_ptr()`)
+and for the current HIP stream; every step of the path runs in the library's
+kernels.  There is no fallback: if the library cannot be loaded the import of
+any entry point raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmoga.so")
+
+MOGA_F32, MOGA_BF16 = 0, 1
+OP_ROUTE, OP_PERMUTE, OP_ATTN_FWD, OP_ATTN_BWD, OP_ROUTE_BWD = range(5)
+
+_c = ctypes
+_vp, _i64, _i32, _f32, _sz = _c.c_void_p, _c.c_int64, _c.c_int, _c.c_float, _c.c_size_t
+_SIGNATURES = {
+    "moga_status_string": (_c.c_char_p, [_i32]),
+    "moga_version": (_i32, []),
+    "moga_workspace_bytes": (_sz, [_i32, _i64, _i32, _i32, _i32, _i32, _i32]),
+    "moga_route": (_i32, [_vp, _i32, _vp, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "moga_permute": (_i32, [_vp, _i64, _i32, _vp, _vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp,
+                            _vp, _vp, _vp, _vp, _sz, _vp]),
+    "moga_group_attn_fwd": (_i32, [_vp, _vp, _vp, _i32, _i64, _i32, _i32, _vp, _i32, _f32, _vp, _vp,
+                                   _vp, _sz, _vp]),
+    "moga_unpermute": (_i32, [_vp, _i32, _vp, _vp, _i64, _i32, _i32, _vp, _vp]),
+    "moga_unpermute_bwd": (_i32, [_vp, _vp, _i32, _vp, _vp, _i64, _i32, _i32, _vp, _vp, _vp]),
+    "moga_group_attn_bwd": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _i64, _i32, _i32, _vp, _i32,
+                                   _f32, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "moga_permute_bwd": (_i32, [_vp, _vp, _vp, _i32, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp]),
+    "moga_route_bwd": (_i32, [_vp, _i32, _vp, _vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _vp, _vp,
+                              _sz, _vp]),
+}
+EXPORTS = tuple(_SIGNATURES)
+
+_lib = None
+
+
+class MogaError(RuntimeError):
+    def __init__(self, fn, status):
+        self.status = status
+        super().__init__(f"{fn} failed: {status_string(status)} ({status})")
+
+
+def load():
+    """Load libmoga.so (building it first only if no built library exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        from . import build as _build
+        _build.build()
+    lib = ctypes.CDLL(LIB_PATH)
+    for name, (res, args) in _SIGNATURES.items():
+        fn = getattr(lib, name)   # AttributeError if an export is missing: fail loudly
+        fn.restype, fn.argtypes = res, args
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load().moga_status_string(int(status)).decode()
+
+
+def version() -> int:
+    return load().moga_version()
+
+
+def workspace_bytes(op, N, H, D, M, d_model, dtype) -> int:
+    return int(load().moga_workspace_bytes(op, N, H, D, M, d_model, dtype))
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return MOGA_F32
+    if t.dtype == torch.bfloat16:
+        return MOGA_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _p(t):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device-resident contiguous tensors only"
+    return t.data_ptr()
+
+
+def _stream(stream):
+    return (stream if stream is not None else torch.cuda.current_stream()).cuda_stream
+
+
+def _ws(nbytes, device):
+    return torch.empty(max(int(nbytes), 16), dtype=torch.uint8, device=device)
+
+
+def _check(fn, status):
+    if status != 0:
+        raise MogaError(fn, status)
+
+
+def moga_route(x, w, bias=None, want_probs=True, want_logits=False, stream=None):
+    """-> (group int32 [N], gate f32 [N], probs f32 [N, M] | None, logits f32 [N, M] | None)"""
+    N, d = x.shape
+    M = w.shape[0]
+    dev = x.device
+    group = torch.empty(N, dtype=torch.int32, device=dev)
+    gate = torch.empty(N, dtype=torch.float32, device=dev)
+    probs = torch.empty((N, M), dtype=torch.float32, device=dev) if want_probs else None
+    logits = torch.empty((N, M), dtype=torch.float32, device=dev) if want_logits else None
+    st = load().moga_route(_p(x), _dt(x), _p(w), _p(bias), N, d, M, _p(group), _p(gate), _p(probs),
+                           _p(logits), None, 0, _stream(stream))
+    _check("moga_route", st)
+    return group, gate, probs, logits
+
+
+def moga_permute(group, M, q=None, k=None, v=None, stream=None):
+    """-> dict(counts, cu_seqlens, max_seqlen, perm, inv_perm[, qh, kh, vh])"""
+    N = group.shape[0]
+    dev = group.device
+    i32 = dict(dtype=torch.int32, device=dev)
+    out = {
+        "counts": torch.empty(M, **i32), "cu_seqlens": torch.empty(M + 1, **i32),
+        "max_seqlen": torch.empty(1, **i32), "perm": torch.empty(N, **i32),
+        "inv_perm": torch.empty(N, **i32),
+    }
+    H = D = 0
+    dt = MOGA_F32
+    if q is not None:
+        _, H, D = q.shape
+        dt = _dt(q)
+        for name, t in (("qh", q), ("kh", k), ("vh", v)):
+            out[name] = torch.empty((H, N, D), dtype=t.dtype, device=dev)
+    nws = workspace_bytes(OP_PERMUTE, N, H, D, M, 0, dt)
+    ws = _ws(nws, dev)
+    st = load().moga_permute(_p(group), N, M, _p(q), _p(k), _p(v), dt, H, D, _p(out["counts"]),
+                             _p(out["cu_seqlens"]), _p(out["max_seqlen"]), _p(out["perm"]),
+                             _p(out["inv_perm"]), _p(out.get("qh")), _p(out.get("kh")),
+                             _p(out.get("vh")), _p(ws), ws.numel(), _stream(stream))
+    _check("moga_permute", st)
+    return out
+
+
+def moga_group_attn_fwd(qh, kh, vh, cu_seqlens, softmax_scale, stream=None, out=None, lse=None):
+    """-> (oh [H, N, D], lse f32 [H, N])"""
+    H, N, D = qh.shape
+    M = cu_seqlens.shape[0] - 1
+    oh = out if out is not None else torch.empty_like(qh)
+    lse = lse if lse is not None else torch.empty((H, N), dtype=torch.float32, device=qh.device)
+    st = load().moga_group_attn_fwd(_p(qh), _p(kh), _p(vh), _dt(qh), N, H, D, _p(cu_seqlens), M,
+                                    float(softmax_scale), _p(oh), _p(lse), None, 0, _stream(stream))
+    _check("moga_group_attn_fwd", st)
+    return oh, lse
+
+
+def moga_unpermute(oh, perm, gate=None, stream=None, out=None):
+    """-> o [N, H, D]"""
+    H, N, D = oh.shape
+    o = out if out is not None else torch.empty((N, H, D), dtype=oh.dtype, device=oh.device)
+    st = load().moga_unpermute(_p(oh), _dt(oh), _p(perm), _p(gate), N, H, D, _p(o), _stream(stream))
+    _check("moga_unpermute", st)
+    return o
+
+
+def moga_unpermute_bwd(d_o, oh, perm, gate, stream=None):
+    """-> (d_oh [H, N, D], d_gate f32 [N])"""
+    H, N, D = oh.shape
+    d_oh = torch.empty_like(oh)
+    d_gate = torch.empty(N, dtype=torch.float32, device=oh.device)
+    st = load().moga_unpermute_bwd(_p(d_o), _p(oh), _dt(oh), _p(perm), _p(gate), N, H, D, _p(d_oh),
+                                   _p(d_gate), _stream(stream))
+    _check("moga_unpermute_bwd", st)
+    return d_oh, d_gate
+
+
+def moga_group_attn_bwd(d_oh, qh, kh, vh, oh, lse, cu_seqlens, softmax_scale, stream=None):
+    """-> (d_qh, d_kh, d_vh) each [H, N, D]"""
+    H, N, D = qh.shape
+    M = cu_seqlens.shape[0] - 1
+    d_qh, d_kh, d_vh = torch.empty_like(qh), torch.empty_like(kh), torch.empty_like(vh)
+    ws = _ws(workspace_bytes(OP_ATTN_BWD, N, H, D, M, 0, _dt(qh)), qh.device)
+    st = load().moga_group_attn_bwd(_p(d_oh), _p(qh), _p(kh), _p(vh), _p(oh), _p(lse), _dt(qh), N, H, D,
+                                    _p(cu_seqlens), M, float(softmax_scale), _p(d_qh), _p(d_kh),
+                                    _p(d_vh), _p(ws), ws.numel(), _stream(stream))
+    _check("moga_group_attn_bwd", st)
+    return d_qh, d_kh, d_vh
+
+
+def moga_permute_bwd(d_qh, d_kh, d_vh, perm, stream=None):
+    """-> (d_q, d_k, d_v) each [N, H, D]"""
+    H, N, D = d_qh.shape
+    mk = lambda t: torch.empty((N, H, D), dtype=t.dtype, device=t.device)
+    d_q, d_k, d_v = mk(d_qh), mk(d_kh), mk(d_vh)
+    st = load().moga_permute_bwd(_p(d_qh), _p(d_kh), _p(d_vh), _dt(d_qh), _p(perm), N, H, D, _p(d_q),
+                                 _p(d_k), _p(d_v), _stream(stream))
+    _check("moga_permute_bwd", st)
+    return d_q, d_k, d_v
+
+
+def moga_route_bwd(x, w, probs, group, gate, d_gate, want_dx=False, stream=None):
+    """-> (d_w f32 [M, d_model], d_x f32 [N, d_model] | None)"""
+    N, d = x.shape
+    M = w.shape[0]
+    d_w = torch.empty((M, d), dtype=torch.float32, device=x.device)
+    d_x = torch.empty((N, d), dtype=torch.float32, device=x.device) if want_dx else None
+    ws = _ws(workspace_bytes(OP_ROUTE_BWD, N, 0, 0, M, d, _dt(x)), x.device)
+    st = load().moga_route_bwd(_p(x), _dt(x), _p(w), _p(probs), _p(group), _p(gate), _p(d_gate), N, d, M,
+                               _p(d_w), _p(d_x), _p(ws), ws.numel(), _stream(stream))
+    _check("moga_route_bwd", st)
+    return d_w, d_x
+
+
+def moga_forward(x, w, q, k, v, softmax_scale, want_probs=True, stream=None):
+    """Alg. 1 end to end: the four forward calls in order on one stream.  Returns a dict."""
+    group, gate, probs, _ = moga_route(x, w, want_probs=want_probs, stream=stream)
+    pm = moga_permute(group, w.shape[0], q, k, v, stream=stream)
+    oh, lse = moga_group_attn_fwd(pm["qh"], pm["kh"], pm["vh"], pm["cu_seqlens"], softmax_scale,
+                                  stream=stream)
+    o = moga_unpermute(oh, pm["perm"], gate, stream=stream)
+    pm.update({"group": group, "gate": gate, "probs": probs, "oh": oh, "lse": lse, "o": o})
+    return pm
+
+
+def moga_backward(fwd, x, w, d_o, softmax_scale, want_dx=False, stream=None):
+    """Backward of `moga_forward`: the four backward calls in reverse order.  Returns a dict."""
+    d_oh, d_gate = moga_unpermute_bwd(d_o, fwd["oh"], fwd["perm"], fwd["gate"], stream=stream)
+    d_qh, d_kh, d_vh = moga_group_attn_bwd(d_oh, fwd["qh"], fwd["kh"], fwd["vh"], fwd["oh"], fwd["lse"],
+                                           fwd["cu_seqlens"], softmax_scale, stream=stream)
+    d_q, d_k, d_v = moga_permute_bwd(d_qh, d_kh, d_vh, fwd["perm"], stream=stream)
+    d_w, d_x = moga_route_bwd(x, w, fwd["probs"], fwd["group"], fwd["gate"], d_gate, want_dx=want_dx,
+                              stream=stream)
+    return {"d_q": d_q, "d_k": d_k, "d_v": d_v, "d_w": d_w, "d_x": d_x, "d_gate": d_gate,
+            "d_oh": d_oh, "d_qh": d_qh, "d_kh": d_kh, "d_vh": d_vh}

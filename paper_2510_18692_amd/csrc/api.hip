@@ -1,0 +1,30 @@
+// Host-only entry points of the C ABI: status strings, version, workspace sizes.
+#include "moga_common.h"
+
+extern "C" size_t moga_permute_ws_bytes(int64_t N, int M);
+extern "C" size_t moga_route_bwd_ws_bytes(int64_t N, int M, int d_model);
+extern "C" size_t moga_attn_bwd_ws_bytes(int64_t N, int H, int D, int dtype);
+
+extern "C" const char* moga_status_string(int status) {
+  switch (status) {
+    case MOGA_OK: return "MOGA_OK";
+    case MOGA_ERR_INVALID_ARG: return "MOGA_ERR_INVALID_ARG";
+    case MOGA_ERR_UNSUPPORTED: return "MOGA_ERR_UNSUPPORTED";
+    case MOGA_ERR_WORKSPACE: return "MOGA_ERR_WORKSPACE";
+    case MOGA_ERR_HIP: return "MOGA_ERR_HIP";
+    default: return "MOGA_ERR_UNKNOWN";
+  }
+}
+
+extern "C" int moga_version(void) { return 100; }
+
+extern "C" size_t moga_workspace_bytes(int op, int64_t N, int H, int D, int M, int d_model,
+                                       int dtype) {
+  if (N <= 0 || M < 1) return 0;
+  switch (op) {
+    case MOGA_OP_PERMUTE: return moga_permute_ws_bytes(N, M);
+    case MOGA_OP_ATTN_BWD: return moga_attn_bwd_ws_bytes(N, H, D, dtype);
+    case MOGA_OP_ROUTE_BWD: return moga_route_bwd_ws_bytes(N, M, d_model);
+    default: return 0;
+  }
+}

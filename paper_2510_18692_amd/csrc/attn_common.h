@@ -1,0 +1,88 @@
+// Pieces shared by the forward and backward group-attention kernels.
+#pragma once
+
+#include "moga_common.h"
+
+namespace moga {
+
+constexpr int kHeadDim = 128;  // head_dim of the bf16 MFMA kernels
+
+// Tile schedule.  Every group g with n_g rows contributes ceil(n_g / rows_per_tile) tiles;
+// tiles never straddle a group boundary.  `tile` is a flat index over all groups in order.
+// Every thread of the block must call this (it contains block-wide barriers).  Returns false
+// when `tile` lies beyond the last real tile (the grid is sized from an upper bound because
+// the group sizes live on the device).
+struct TileInfo {
+  int group;      // group id
+  int row_begin;  // first row of the group (sorted slot)
+  int row_end;    // one past the last row of the group
+  int tile_row;   // first row of this tile
+};
+
+__device__ __forceinline__ bool find_tile(const int32_t* __restrict__ cu_seqlens, int M,
+                                          int rows_per_tile, int tile, int* s_start /*[M+1]*/,
+                                          int* s_found, TileInfo& out) {
+  const int lane = threadIdx.x & 63;
+  if (threadIdx.x < 64) {
+    int running = 0;
+    for (int g0 = 0; g0 < M; g0 += 64) {
+      const int g = g0 + lane;
+      const int n = g < M ? cu_seqlens[g + 1] - cu_seqlens[g] : 0;
+      const int t = (n + rows_per_tile - 1) / rows_per_tile;
+      int incl = t;
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const int up = __shfl_up(incl, o, kWave);
+        if (lane >= o) incl += up;
+      }
+      if (g < M) s_start[g] = running + incl - t;
+      running += __shfl(incl, 63, kWave);
+    }
+    if (lane == 0) { s_start[M] = running; *s_found = -1; }
+  }
+  __syncthreads();
+  for (int g = threadIdx.x; g < M; g += blockDim.x)
+    if (s_start[g] <= tile && tile < s_start[g + 1]) *s_found = g;
+  __syncthreads();
+  const int g = *s_found;
+  if (g < 0) return false;
+  out.group = g;
+  out.row_begin = cu_seqlens[g];
+  out.row_end = cu_seqlens[g + 1];
+  out.tile_row = out.row_begin + (tile - s_start[g]) * rows_per_tile;
+  return true;
+}
+
+// Upper bound on the number of tiles for N rows in M groups (host side).
+inline int64_t max_tiles(int64_t N, int M, int rows_per_tile) {
+  return (N + rows_per_tile - 1) / rows_per_tile + M;
+}
+
+// Work item of a block: blocks are dealt round-robin to the 8 XCDs by the hardware, so block
+// b runs on XCD b % 8.  Give each XCD one contiguous eighth of the (head-major) work list, so
+// that the K/V tiles of a head are streamed through a single L2.
+__device__ __forceinline__ int64_t xcd_work_index(int64_t block, int64_t total) {
+  const int64_t per = (total + 7) / 8;
+  return (block & 7) * per + (block >> 3);
+}
+
+// Row permutation that makes the 32x32 MFMA accumulator registers of a lane hold eight
+// consecutive contraction indices: swap bits 2 and 3 of the row index.
+__device__ __forceinline__ int swap_bits_2_3(int x) {
+  return (x & ~12) | ((x & 4) << 1) | ((x & 8) >> 1);
+}
+
+// Transposed LDS read: the 16 lanes of a block each point at 4 consecutive bf16; lane i gets,
+// for e = 0..3, element i%4 of the 4 bf16 that lane 4e + i/4 pointed at.
+__device__ __forceinline__ short4_t lds_read_tr16(const unsigned short* p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (short4_t __attribute__((address_space(3)))*)(p));
+}
+
+__device__ __forceinline__ bf16x8_t concat_tr(short4_t lo, short4_t hi) {
+  typedef short short8_t __attribute__((ext_vector_type(8)));
+  short8_t s = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+  return __builtin_bit_cast(bf16x8_t, s);
+}
+
+}  // namespace moga

@@ -1,0 +1,89 @@
+"""The C-ABI library loads and exports every symbol the header declares; argument errors
+are reported as status codes without touching a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2510_18692_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "moga.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(moga_[a-z_]+)\s*\(", text)))
+
+
+def test_header_declares_the_expected_entry_points():
+    names = declared_functions()
+    for n in ("moga_route", "moga_permute", "moga_group_attn_fwd", "moga_group_attn_bwd",
+              "moga_unpermute", "moga_unpermute_bwd", "moga_permute_bwd", "moga_route_bwd",
+              "moga_workspace_bytes", "moga_status_string", "moga_version"):
+        assert n in names
+
+
+def test_library_exports_every_declared_symbol_and_binding_covers_them():
+    lib = binding.load()
+    for n in declared_functions():
+        assert hasattr(lib, n), n
+        assert n in binding.EXPORTS, n
+
+
+def test_status_strings_and_version():
+    assert binding.status_string(0) == "MOGA_OK"
+    assert binding.status_string(-1) == "MOGA_ERR_INVALID_ARG"
+    assert binding.status_string(-2) == "MOGA_ERR_UNSUPPORTED"
+    assert binding.status_string(-3) == "MOGA_ERR_WORKSPACE"
+    assert binding.status_string(-4) == "MOGA_ERR_HIP"
+    assert binding.status_string(17) == "MOGA_ERR_UNKNOWN"
+    assert binding.version() >= 100
+
+
+def test_workspace_sizes_are_monotone_and_zero_for_empty_input():
+    wb = binding.workspace_bytes
+    assert wb(binding.OP_PERMUTE, 0, 40, 128, 32, 0, 1) == 0
+    a = wb(binding.OP_PERMUTE, 4096, 2, 64, 8, 0, 0)
+    b = wb(binding.OP_PERMUTE, 580320, 40, 128, 32, 0, 1)
+    assert 0 < a <= b
+    assert wb(binding.OP_ROUTE_BWD, 99840, 0, 0, 16, 5120, 1) >= 16 * 5120 * 4
+    assert wb(binding.OP_ATTN_BWD, 99840, 40, 128, 16, 0, 1) >= 99840 * 40 * 4
+    assert wb(binding.OP_ROUTE, 99840, 0, 0, 16, 5120, 1) == 0
+
+
+def test_invalid_arguments_return_status_codes_without_a_gpu():
+    lib = binding.load()
+    fake = ctypes.c_void_p(0x1000)   # aligned, never dereferenced: validation fails first
+    # NULL required pointer
+    assert lib.moga_route(None, 1, fake, None, 8, 64, 4, fake, fake, None, None, None, 0, None) == -1
+    # too many groups, unknown dtype
+    assert lib.moga_route(fake, 1, fake, None, 8, 64, 257, fake, fake, None, None, None, 0, None) == -2
+    assert lib.moga_route(fake, 7, fake, None, 8, 64, 4, fake, fake, None, None, None, 0, None) == -2
+    # negative N
+    assert lib.moga_route(fake, 1, fake, None, -1, 64, 4, fake, fake, None, None, None, 0, None) == -1
+    # misaligned tensor
+    assert lib.moga_route(ctypes.c_void_p(0x1004), 1, fake, None, 8, 64, 4, fake, fake, None, None,
+                          None, 0, None) == -1
+    # empty input is a successful no-op
+    assert lib.moga_route(None, 1, None, None, 0, 64, 4, None, None, None, None, None, 0, None) == 0
+    assert lib.moga_unpermute(None, 1, None, None, 0, 40, 128, None, None) == 0
+    # unsupported head_dim / dtype pairs
+    assert lib.moga_group_attn_fwd(fake, fake, fake, 1, 128, 2, 64, fake, 4, 0.1, fake, fake, None, 0,
+                                   None) == -2
+    assert lib.moga_group_attn_fwd(fake, fake, fake, 0, 128, 2, 96, fake, 4, 0.1, fake, fake, None, 0,
+                                   None) == -2
+    assert lib.moga_unpermute(fake, 1, fake, None, 16, 2, 64, fake, None) == -2
+    # bad softmax scale
+    assert lib.moga_group_attn_fwd(fake, fake, fake, 1, 128, 2, 128, fake, 4, 0.0, fake, fake, None, 0,
+                                   None) == -1
+    assert lib.moga_group_attn_fwd(fake, fake, fake, 1, 128, 2, 128, fake, 4, float("nan"), fake, fake,
+                                   None, 0, None) == -1
+    # short workspace
+    assert lib.moga_permute(fake, 4096, 8, None, None, None, 0, 0, 0, fake, fake, fake, fake, fake,
+                            None, None, None, fake, 4, None) == -3
+    assert lib.moga_permute(fake, 4096, 8, None, None, None, 0, 0, 0, fake, fake, fake, fake, fake,
+                            None, None, None, None, 0, None) == -3
+    assert lib.moga_route_bwd(fake, 1, fake, fake, fake, fake, fake, 4096, 128, 8, fake, None, fake, 16,
+                              None) == -3
