@@ -1,0 +1,172 @@
+"""GPU parity of the backward path against the CPU oracle, call by call through the C ABI.
+
+Stage inputs come from the seeded generators or from the oracle's own forward (never from a
+GPU stage); gradients are compared element by element.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import moga_oracle as orc
+from paper_2510_18692_amd import binding as mg
+from paper_2510_18692_amd import workloads as wl
+from tests import parity as P
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def tdt(dtype):
+    return torch.float32 if dtype == "f32" else torch.bfloat16
+
+
+def check(got, ref, what, dtype):
+    if dtype == "f32":
+        return P.assert_close_f32(got, ref, what)
+    # bf16 gradients: scale-free bounds (no absolute bound is stated for gradients)
+    rm, rl = P.rel_max(got, ref), P.rel_l2(got, ref)
+    assert rm <= P.BF16_REL_MAX, f"{what}: max|a-b|/max|b| = {rm:.3e}"
+    assert rl <= P.BF16_REL_L2, f"{what}: l2 rel = {rl:.3e}"
+    return rm, rl
+
+
+@pytest.mark.parametrize("N,H,D,dtype", [(4096, 2, 64, "f32"), (999, 3, 128, "f32"), (3001, 12, 128, "bf16")])
+def test_unpermute_bwd_matches_oracle(N, H, D, dtype):
+    say(f"unpermute_bwd N={N} H={H} D={D} {dtype}")
+    g = torch.Generator().manual_seed(N + 2)
+    oh = torch.randn((H, N, D), generator=g).to(tdt(dtype))
+    d_o = torch.randn((N, H, D), generator=g).to(tdt(dtype))
+    perm = torch.randperm(N, generator=g).to(torch.int32)
+    gate = torch.rand(N, generator=g)
+    A = np.transpose(P.to64(oh), (1, 0, 2))                      # sorted order [N, H, D]
+    A_tok = np.empty_like(A)
+    A_tok[perm.numpy()] = A
+    ref_dgate = (P.to64(d_o) * A_tok).sum(axis=(1, 2))
+    ref_dA = (P.to64(d_o) * P.to64(gate)[:, None, None])[perm.numpy()]
+    d_oh, d_gate = mg.moga_unpermute_bwd(d_o.cuda(), oh.cuda(), perm.cuda(), gate.cuda())
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(P.to64(d_gate), ref_dgate, rtol=2e-5, atol=2e-4 if dtype == "f32" else 1e-3)
+    np.testing.assert_allclose(P.unhat(d_oh), ref_dA, rtol=2e-7 if dtype == "f32" else 2 ** -8, atol=0)
+
+
+@pytest.mark.parametrize("N,H,D,dtype", [(4096, 2, 64, "f32"), (1000, 3, 128, "bf16")])
+def test_permute_bwd_is_the_inverse_gather(N, H, D, dtype):
+    g = torch.Generator().manual_seed(N + 3)
+    ts = [torch.randn((H, N, D), generator=g).to(tdt(dtype)) for _ in range(3)]
+    perm = torch.randperm(N, generator=g).to(torch.int32)
+    outs = mg.moga_permute_bwd(*(t.cuda() for t in ts), perm.cuda())
+    torch.cuda.synchronize()
+    for t, o in zip(ts, outs):
+        expect = torch.empty((N, H, D), dtype=t.dtype)
+        expect[perm.long()] = t.permute(1, 0, 2)
+        assert torch.equal(o.cpu(), expect)
+
+
+def attn_bwd_case(sizes, H, D, dtype, seed):
+    N = int(sum(sizes))
+    g = torch.Generator().manual_seed(seed)
+    q, k, v, dA = (torch.randn((N, H, D), generator=g).to(tdt(dtype)) for _ in range(4))
+    cu = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    return q, k, v, dA, cu, D ** -0.5
+
+
+@pytest.mark.parametrize("sizes,H,D,dtype", [
+    ([512] * 8, 2, 64, "f32"),
+    ([1, 0, 65, 130, 31, 0, 64, 200], 2, 64, "f32"),
+    ([300, 0, 1, 129, 257, 64, 2, 511], 3, 128, "bf16"),
+    ([2049, 1500, 17], 2, 128, "bf16"),
+    ([40], 1, 128, "bf16"),
+])
+def test_group_attention_backward_matches_oracle(sizes, H, D, dtype):
+    say(f"attn bwd sizes={sizes} H={H} D={D} {dtype}")
+    q, k, v, dA, cu, scale = attn_bwd_case(sizes, H, D, dtype, seed=len(sizes) + D + 1)
+    q64, k64, v64, dA64 = (P.to64(t) for t in (q, k, v, dA))
+    A, lse = orc.group_attention(q64, k64, v64, cu, scale)
+    dQ, dK, dV = orc.group_attention_bwd(q64, k64, v64, dA64, cu, scale)
+    tohat = lambda t: t.permute(1, 0, 2).contiguous().cuda()
+    # forward outputs the backward consumes are the oracle's, rounded to the storage type
+    oh = torch.from_numpy(P.hat(A)).to(tdt(dtype)).cuda()
+    lse_d = torch.from_numpy(np.ascontiguousarray(lse.T)).float().cuda()
+    d_qh, d_kh, d_vh = mg.moga_group_attn_bwd(tohat(dA), tohat(q), tohat(k), tohat(v), oh, lse_d,
+                                              torch.from_numpy(cu).cuda(), scale)
+    torch.cuda.synchronize()
+    for name, got, ref in (("dQ", d_qh, dQ), ("dK", d_kh, dK), ("dV", d_vh, dV)):
+        e = check(P.unhat(got), ref, name, dtype)
+        say(f"  {name} error {e}")
+        assert np.all(np.isfinite(P.unhat(got)))
+
+
+@pytest.mark.parametrize("N,d,M,dtype,want_dx", [(4096, 128, 8, "f32", True), (5000, 1536, 8, "bf16", False),
+                                                 (777, 200, 40, "bf16", True), (130000, 64, 5, "bf16", False)])
+def test_route_bwd_matches_oracle(N, d, M, dtype, want_dx):
+    say(f"route_bwd N={N} d={d} M={M} {dtype}")
+    g = torch.Generator().manual_seed(N + d)
+    x = torch.randn((N, d), generator=g).to(tdt(dtype))
+    w = torch.randn((M, d), generator=g) * (2.0 / math.sqrt(d))
+    d_gate = torch.randn(N, generator=g)
+    rt = orc.route(P.to64(x), P.to64(w))
+    probs = torch.from_numpy(rt["probs"])
+    group = torch.from_numpy(rt["group"])
+    gate = torch.from_numpy(rt["gate"])
+    dW, dX, _ = orc.route_bwd(P.to64(x), P.to64(w), rt["probs"], rt["group"], rt["gate"], P.to64(d_gate),
+                              want_dx=want_dx)
+    d_w, d_x = mg.moga_route_bwd(x.cuda(), w.cuda(), probs.cuda(), group.cuda(), gate.cuda(), d_gate.cuda(),
+                                 want_dx=want_dx)
+    torch.cuda.synchronize()
+    e = P.assert_close_f32(P.to64(d_w), dW, "dW")
+    say(f"  dW rel err {e:.3e}")
+    np.testing.assert_allclose(P.to64(d_w).sum(0), 0.0, atol=1e-3 * np.abs(dW).max())
+    if want_dx:
+        P.assert_close_f32(P.to64(d_x), dX, "dX")
+
+
+def run_fwd_bwd(w):
+    inp = wl.make_inputs(w, "cpu")
+    X, W, Q, K, V, dO = (P.to64(inp[k]) for k in ("X", "W", "Q", "K", "V", "dO"))
+    f = orc.moga_forward(X, W, Q, K, V, w.scale)
+    b = orc.moga_backward(f, X, W, dO, w.scale)
+    d = {k: inp[k].cuda() for k in ("X", "W", "Q", "K", "V", "dO")}
+    fg = mg.moga_forward(d["X"], d["W"], d["Q"], d["K"], d["V"], w.scale)
+    bg = mg.moga_backward(fg, d["X"], d["W"], d["dO"], w.scale)
+    torch.cuda.synchronize()
+    return f, b, fg, bg
+
+
+def test_config1_fp32_forward_backward_every_element():
+    """C1 shapes with backward: the strict <= 1e-4 gradient check on the fp32 path."""
+    w = wl.WORKLOADS["C1b"]
+    say("C1 fwd+bwd")
+    f, b, fg, bg = run_fwd_bwd(w)
+    assert not P.check_assignment(fg["group"].cpu().numpy(), f)
+    for name, key in (("dQ", "d_q"), ("dK", "d_k"), ("dV", "d_v"), ("dW", "d_w")):
+        e = P.assert_close_f32(P.to64(bg[key]), b[name], name)
+        say(f"  {name} rel err {e:.3e}")
+    np.testing.assert_allclose(P.to64(bg["d_gate"]), b["d_gate"], rtol=1e-4, atol=1e-4 * np.abs(b["d_gate"]).max())
+
+
+def test_config5_shape_bf16_forward_backward_reduced_tokens():
+    """C5's widths (40 heads, head_dim 128, d_model 5120, M = 16, Zipf mixture) on 4 latent frames."""
+    w = wl.scaled(wl.WORKLOADS["C5"], N=4 * 1560)
+    say("C5 (4 frames) fwd+bwd")
+    f, b, fg, bg = run_fwd_bwd(w)
+    bad = P.check_assignment(fg["group"].cpu().numpy(), f)
+    say("  counts", f["counts"].tolist())
+    assert not bad, "reduced config: no near-tie expected"
+    for name, key in (("dQ", "d_q"), ("dK", "d_k"), ("dV", "d_v")):
+        say(f"  {name}", check(P.to64(bg[key]), b[name], name, "bf16"))
+    rl = P.rel_l2(P.to64(bg["d_w"]), b["dW"])
+    say(f"  dW l2 rel {rl:.3e}")
+    assert rl <= 5e-3
+    np.testing.assert_allclose(P.to64(bg["d_w"]).sum(0), 0.0, atol=2e-3 * np.abs(b["dW"]).max())
+
+
+def test_single_group_backward_has_zero_router_gradient():
+    w = wl.scaled(wl.WORKLOADS["C1b"], N=600, M=1)
+    f, b, fg, bg = run_fwd_bwd(w)
+    assert torch.all(bg["d_w"] == 0)
+    P.assert_close_f32(P.to64(bg["d_q"]), b["dQ"], "dQ (M=1)")
