@@ -1,0 +1,222 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoGA hot path on one MI355X.
+
+One "step" is one pass of the whole path over one batch of synthetic video tokens:
+route -> permute -> group attention -> unpermute, and (for workloads with backward)
+unpermute_bwd -> group attention bwd -> permute_bwd -> route_bwd.  Inputs are resident in
+HBM before the timed region.  The default workload is the paper-scale context (N = 580,320
+tokens, 40 heads, head_dim 128, d_model 5120, M = 32) forward + backward.
+
+Prints ONE JSON line: whole-job effective TFLOP/s (within-group attention FLOPs only:
+4*H*D*sum n_g^2 forward, 10*H*D*sum n_g^2 backward) as `value`, ms per layer as
+`ms_per_step`, a `roofline` object for the dominant call, per-call figures in `calls`,
+and the CPU oracle timed on a bounded sample in `cpu_baseline`.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, published
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="C4b", help="C1, C1b, C2, C3, C3b, C4, C4b (default), C5")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def algorithmic_work(w, counts):
+    """Per call: (bound, algorithmic bytes or flops per launch).  Bytes follow the method's own
+    data movement: every tensor a call must read or write, once."""
+    from paper_2510_18692_amd import flops
+    N, H, D, d, M = w.N, w.H, w.D, w.d_model, w.M
+    es = 4 if w.dtype == "f32" else 2
+    t = N * H * D * es                      # one [N, H, D] tensor
+    work = {
+        "moga_route": ("hbm", N * d * es + M * d * 4 + 8 * N + (4 * N * M if w.backward else 0)),
+        "moga_permute": ("hbm", 6 * t + 4 * N * 2 + 8 * N + 4 * N),
+        "moga_group_attn_fwd": ("mfma", flops.group_attn_fwd_flops(counts, H, D)),
+        "moga_unpermute": ("hbm", 2 * t + 8 * N),
+    }
+    if w.backward:
+        work.update({
+            "moga_unpermute_bwd": ("hbm", 3 * t + 12 * N),
+            "moga_group_attn_bwd": ("mfma", flops.group_attn_bwd_flops(counts, H, D)),
+            "moga_permute_bwd": ("hbm", 6 * t + 4 * N),
+            "moga_route_bwd": ("hbm", N * d * es + 4 * N * M + 16 * N + M * d * 4),
+        })
+    return work
+
+
+def cpu_baseline(w, budget_s=20.0):
+    """The oracle as it stands, timed on this host on a bounded sample of the same workload."""
+    import numpy as np
+    from oracle import moga_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    rng = np.random.default_rng(7)
+    n_g = max(64, w.N // w.M)                   # one average-size group
+    n_g = min(n_g, 8192)                        # bounded: the score matrix is n_g^2 float64
+    D = w.D
+    q, k, v, dA = (rng.standard_normal((n_g, D)) for _ in range(4))
+    t0 = time.perf_counter()
+    reps = 0
+    fl = 0.0
+    while True:
+        orc.softmax_attention(q, k, v, w.scale)
+        fl += 4.0 * n_g * n_g * D
+        if w.backward:
+            orc.softmax_attention_bwd(q, k, v, dA, w.scale)
+            fl += 10.0 * n_g * n_g * D
+        reps += 1
+        el = time.perf_counter() - t0
+        if el > budget_s or reps >= 50:
+            break
+    # routing sample, reported in the note only
+    nt = min(w.N, 16384)
+    X = rng.standard_normal((nt, w.d_model))
+    W = rng.standard_normal((w.M, w.d_model))
+    t1 = time.perf_counter()
+    orc.route(X, W)
+    t_route = time.perf_counter() - t1
+    return {
+        "value": fl / el / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+        "sample": (f"{reps} x one head of one group of {n_g} tokens (head_dim {D}), "
+                   f"{'forward+backward' if w.backward else 'forward'}, float64 numpy, {el:.1f} s; "
+                   f"routing {nt} tokens took {t_route:.2f} s"),
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
+              "--gpus must be 1. The design notes say how the path would shard by head.",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2510_18692_amd import binding as mg
+    from paper_2510_18692_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    mg.load()
+    w = wl.WORKLOADS[args.workload]
+    torch.cuda.set_device(0)
+    inp = wl.make_inputs(w, "cuda")
+    X, W, Q, K, V = inp["X"], inp["W"], inp["Q"], inp["K"], inp["V"]
+    dO = inp.get("dO")
+    torch.cuda.synchronize()
+
+    names = ["moga_route", "moga_permute", "moga_group_attn_fwd", "moga_unpermute"]
+    if w.backward:
+        names += ["moga_unpermute_bwd", "moga_group_attn_bwd", "moga_permute_bwd", "moga_route_bwd"]
+
+    def step(events=None):
+        def mark(i):
+            if events is not None:
+                events[i].record()
+        mark(0)
+        group, gate, probs, _ = mg.moga_route(X, W, want_probs=w.backward)
+        mark(1)
+        pm = mg.moga_permute(group, w.M, Q, K, V)
+        mark(2)
+        oh, lse = mg.moga_group_attn_fwd(pm["qh"], pm["kh"], pm["vh"], pm["cu_seqlens"], w.scale)
+        mark(3)
+        o = mg.moga_unpermute(oh, pm["perm"], gate)
+        mark(4)
+        out = {"counts": pm["counts"], "o": o}
+        if w.backward:
+            d_oh, d_gate = mg.moga_unpermute_bwd(dO, oh, pm["perm"], gate)
+            mark(5)
+            d_qh, d_kh, d_vh = mg.moga_group_attn_bwd(d_oh, pm["qh"], pm["kh"], pm["vh"], oh, lse,
+                                                      pm["cu_seqlens"], w.scale)
+            mark(6)
+            d_q, d_k, d_v = mg.moga_permute_bwd(d_qh, d_kh, d_vh, pm["perm"])
+            mark(7)
+            d_w, _ = mg.moga_route_bwd(X, W, probs, group, gate, d_gate)
+            mark(8)
+            out["d_w"] = d_w
+        return out
+
+    for _ in range(args.warmup):
+        out = step()
+        torch.cuda.synchronize()
+        del out
+    nev = len(names) + 1
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(nev)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    counts = None
+    for s in range(args.steps):
+        out = step(evs[s])
+        counts = out["counts"]
+        del out
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+
+    counts = counts.cpu().tolist()
+    work = algorithmic_work(w, counts)
+    calls = {}
+    for i, n in enumerate(names):
+        ms = sum(evs[s][i].elapsed_time(evs[s][i + 1]) for s in range(args.steps)) / args.steps
+        bound, amount = work[n]
+        if bound == "mfma":
+            ach, peak, unit = amount / (ms * 1e-3) / 1e12, PEAK_BF16_TFLOPS, "TFLOP/s"
+            if w.dtype == "f32":
+                peak = 157.3
+        else:
+            ach, peak, unit = amount / (ms * 1e-3) / 1e9, PEAK_HBM_GBS, "GB/s"
+        calls[n] = {"ms": round(ms, 4), "bound": bound, "achieved": round(ach, 2), "peak": peak,
+                    "unit": unit, "frac": round(ach / peak, 4)}
+    dominant = max(calls, key=lambda n: calls[n]["ms"])
+    roof = {k: calls[dominant][k] for k in ("bound", "achieved", "peak", "unit", "frac")}
+    roof["kernel"] = dominant
+    roof["ms"] = calls[dominant]["ms"]
+    roof["traffic"] = None
+
+    from paper_2510_18692_amd import flops
+    total_flops = flops.group_attn_fwd_flops(counts, w.H, w.D)
+    if w.backward:
+        total_flops += flops.group_attn_bwd_flops(counts, w.H, w.D)
+    value = total_flops / (ms_per_step * 1e-3) / 1e12
+
+    line = {
+        "metric": "MoGA layer effective TFLOP/s (within-group attention FLOPs, "
+                  + ("fwd+bwd" if w.backward else "fwd") + "); ms/layer in ms_per_step",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"{w.name}: N={w.N} ({w.grid} latent grid), H={w.H}, D={w.D}, "
+                               f"d_model={w.d_model}, M={w.M}, {w.hidden} hidden states, "
+                               + ("forward+backward" if w.backward else "forward"),
+                   "group_sizes": {"min": min(counts), "max": max(counts),
+                                   "sum_sq_over_N2": round(flops.sum_sq(counts) / float(w.N) ** 2, 5)}},
+        "roofline": roof,
+        "calls": calls,
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()
