@@ -11,7 +11,10 @@
 // Both MFMA kernels keep the contraction index of the second product in the accumulator
 // registers of the first (row permutation of the LDS operand), and read the transposed
 // operands (dO^T, Q^T, K^T) from row-major LDS tiles with the transposing LDS read.
+#include <stdlib.h>
+
 #include "attn_common.h"
+#include "attn_bwd_pipe.h"
 
 namespace moga {
 
@@ -23,7 +26,9 @@ constexpr int kBwdStride = kHeadDim + 8;  // bf16 per LDS row
 template <int LPR, bool BF16>
 __global__ __launch_bounds__(256) void attn_bwd_delta_kernel(const uintx4_t* __restrict__ d_oh,
                                                              const uintx4_t* __restrict__ oh,
-                                                             int64_t rows, float* __restrict__ delta) {
+                                                             const float* __restrict__ lse, int64_t rows,
+                                                             float* __restrict__ delta,
+                                                             float* __restrict__ lse2) {
   const int64_t row = ((int64_t)blockIdx.x * 256 + threadIdx.x) / LPR;
   const int part = threadIdx.x % LPR;
   float s = 0.f;
@@ -42,7 +47,10 @@ __global__ __launch_bounds__(256) void attn_bwd_delta_kernel(const uintx4_t* __r
   }
 #pragma unroll
   for (int o = LPR / 2; o > 0; o >>= 1) s += __shfl_xor(s, o, kWave);
-  if (row < rows && part == 0) delta[row] = s;
+  if (row < rows && part == 0) {
+    delta[row] = s;
+    if (lse2) lse2[row] = lse[row] * kLog2e;   // the bf16 kernels exponentiate in base 2
+  }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -462,7 +470,7 @@ using namespace moga;
 extern "C" size_t moga_attn_bwd_ws_bytes(int64_t N, int H, int D, int dtype) {
   (void)D; (void)dtype;
   if (N <= 0 || H < 1) return 0;
-  return (size_t)N * (size_t)H * sizeof(float);   // delta
+  return 2 * (size_t)N * (size_t)H * sizeof(float);   // delta, lse * log2(e)
 }
 
 extern "C" int moga_group_attn_bwd(const void* d_oh, const void* qh, const void* kh, const void* vh,
@@ -488,35 +496,43 @@ extern "C" int moga_group_attn_bwd(const void* d_oh, const void* qh, const void*
   float* delta = (float*)ws;
   const int64_t rows = N * (int64_t)H;
   if (dtype == MOGA_BF16) {
+    float* lse2 = delta + rows;
     attn_bwd_delta_kernel<16, true><<<(unsigned)((rows * 16 + 255) / 256), 256, 0, st>>>(
-        (const uintx4_t*)d_oh, (const uintx4_t*)oh, rows, delta);
+        (const uintx4_t*)d_oh, (const uintx4_t*)oh, lse, rows, delta, lse2);
+    const char* ev = getenv("MOGA_BWD_VARIANT");
+    const int variant = ev ? atoi(ev) : 0;
     {
       const int64_t tiles = max_tiles(N, M, 128);
       const int64_t blocks = (tiles * H + 7) / 8 * 8;
       if (blocks >= ((int64_t)1 << 31)) return MOGA_ERR_UNSUPPORTED;
-      attn_bwd_dkdv_bf16_kernel<<<(unsigned)blocks, 256, 0, st>>>(
-          (const unsigned short*)d_oh, (const unsigned short*)qh, (const unsigned short*)kh,
-          (const unsigned short*)vh, lse, delta, cu_seqlens, M, N, H, softmax_scale, (int)tiles,
-          (unsigned short*)d_kh, (unsigned short*)d_vh);
+      if (variant == 1)
+        attn_bwd_dkdv_bf16_kernel<<<(unsigned)blocks, 256, 0, st>>>(
+            (const unsigned short*)d_oh, (const unsigned short*)qh, (const unsigned short*)kh,
+            (const unsigned short*)vh, lse, delta, cu_seqlens, M, N, H, softmax_scale, (int)tiles,
+            (unsigned short*)d_kh, (unsigned short*)d_vh);
+      else
+        attn_bwd_dkdv_pipe_kernel<4><<<(unsigned)blocks, 256, 0, st>>>(
+            (const unsigned short*)d_oh, (const unsigned short*)qh, (const unsigned short*)kh,
+            (const unsigned short*)vh, lse2, delta, cu_seqlens, M, N, H, softmax_scale, (int)tiles,
+            (unsigned short*)d_kh, (unsigned short*)d_vh);
     }
     {
-      const bool big = N * (int64_t)H >= (int64_t)256 * 256 * 4;
-      const int64_t tiles = max_tiles(N, M, big ? 256 : 128);
+      const int64_t tiles = max_tiles(N, M, 256);
       const int64_t blocks = (tiles * H + 7) / 8 * 8;
-      if (big)
+      if (variant == 1)
         attn_bwd_dq_bf16_kernel<2><<<(unsigned)blocks, 256, 0, st>>>(
             (const unsigned short*)d_oh, (const unsigned short*)qh, (const unsigned short*)kh,
             (const unsigned short*)vh, lse, delta, cu_seqlens, M, N, H, softmax_scale, (int)tiles,
             (unsigned short*)d_qh);
       else
-        attn_bwd_dq_bf16_kernel<1><<<(unsigned)blocks, 256, 0, st>>>(
+        attn_bwd_dq_pipe_kernel<8, 1><<<(unsigned)blocks, 512, 0, st>>>(
             (const unsigned short*)d_oh, (const unsigned short*)qh, (const unsigned short*)kh,
-            (const unsigned short*)vh, lse, delta, cu_seqlens, M, N, H, softmax_scale, (int)tiles,
+            (const unsigned short*)vh, lse2, delta, cu_seqlens, M, N, H, softmax_scale, (int)tiles,
             (unsigned short*)d_qh);
     }
   } else {
     attn_bwd_delta_kernel<16, false><<<(unsigned)((rows * 16 + 255) / 256), 256, 0, st>>>(
-        (const uintx4_t*)d_oh, (const uintx4_t*)oh, rows, delta);
+        (const uintx4_t*)d_oh, (const uintx4_t*)oh, lse, rows, delta, nullptr);
     const int64_t tiles = max_tiles(N, M, kF32BM);
     const int64_t blocks = tiles * H;
     if (blocks >= ((int64_t)1 << 31)) return MOGA_ERR_UNSUPPORTED;

@@ -1,0 +1,475 @@
+// bf16 backward kernels of the group attention (head_dim 128) on the LDS ring of attn_pipe.h.
+//
+//   attn_bwd_dq_pipe_kernel   : a wave owns 32*QW query rows (Q, dO fragments, lse, delta and
+//                               the dQ^T accumulators in registers) and sweeps 64-key tiles of
+//                               K and V; three MFMA products per tile (S^T, dP^T, dQ^T).
+//   attn_bwd_dkdv_pipe_kernel : a wave owns 32 key rows (K, V fragments, dK^T and dV^T
+//                               accumulators in registers) and sweeps 64-query tiles of Q, dO,
+//                               lse and delta; four MFMA products per tile (S, dP, dV^T, dK^T).
+// Tiles are streamed global -> LDS by direct-to-LDS loads into a ring of four slots, two tiles
+// ahead; one block-wide barrier per tile; one wave per SIMD (the accumulators need > 256 registers).
+#pragma once
+
+#include "attn_pipe.h"
+
+namespace moga {
+
+__device__ __forceinline__ void lds_dma4_soff(const void* base, unsigned byte_off, unsigned lds_wave_base) {
+  lds_wave_base = __builtin_amdgcn_readfirstlane(lds_wave_base);
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
+               :
+               : "s"(lds_wave_base), "v"(byte_off), "s"(base)
+               : "memory");
+}
+
+__device__ __forceinline__ floatx4_t lds_read_f32x4(unsigned addr) {
+  return *(const floatx4_t __attribute__((address_space(3)))*)(uintptr_t)addr;
+}
+
+// exp2(s*c - lse2) and dS = P * (dP - delta) for the 16 scores of a lane, packed to bf16.
+// `limit`: contraction indices >= limit (relative to the step's first) get P = 0 (MASK only).
+// lse2 / dlt are per register (PER_REG: 16 values, the lane's 16 rows) or one per lane.
+template <bool MASK, bool WANT_P>
+__device__ __forceinline__ void softmax_bwd_regs(const floatx16_t& s, const floatx16_t& dp,
+                                                 const float* lse2, const float* dlt, int stride,
+                                                 float c, int h, int limit, bf16x8_t (&pf)[2],
+                                                 bf16x8_t (&dsf)[2]) {
+#pragma unroll
+  for (int kstep = 0; kstep < 2; ++kstep) {
+    unsigned int pp[4], dd[4];
+#pragma unroll
+    for (int j = 0; j < 8; j += 2) {
+      const int v = 8 * kstep + j;
+      float pa = fast_exp2(fmaf(s[v], c, -lse2[v * stride]));
+      float pb = fast_exp2(fmaf(s[v + 1], c, -lse2[(v + 1) * stride]));
+      if (MASK) {
+        const int idx = 16 * kstep + 8 * h + j;
+        if (idx >= limit) pa = 0.f;
+        if (idx + 1 >= limit) pb = 0.f;
+      }
+      if (WANT_P) pp[j >> 1] = pack_bf16x2(pa, pb);
+      dd[j >> 1] = pack_bf16x2(pa * (dp[v] - dlt[v * stride]), pb * (dp[v + 1] - dlt[(v + 1) * stride]));
+    }
+    if (WANT_P) {
+      const uintx4_t pu = {pp[0], pp[1], pp[2], pp[3]};
+      pf[kstep] = __builtin_bit_cast(bf16x8_t, pu);
+    }
+    const uintx4_t du = {dd[0], dd[1], dd[2], dd[3]};
+    dsf[kstep] = __builtin_bit_cast(bf16x8_t, du);
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// dQ: query-stationary
+// ---------------------------------------------------------------------------------------
+struct DqLane {
+  unsigned k_nat[8];     // K fragment (row = permuted lane row) for d chunk pair ks, slot 0, half 0
+  unsigned k_tr[4][2];   // transposed K read for d tile dt, rows +0 / +4
+  unsigned v_minus_k;    // LDS distance from the K ring to the V ring
+};
+
+// S^T = K Q^T and dP^T = V dO^T for one 32-key half of a tile
+template <int QW>
+__device__ __forceinline__ void dq_scores(const DqLane& ln, unsigned off, const bf16x8_t (&qf)[QW][8],
+                                          const bf16x8_t (&dof)[QW][8], floatx16_t (&s)[QW],
+                                          floatx16_t (&dp)[QW]) {
+#pragma unroll
+  for (int qw = 0; qw < QW; ++qw)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { s[qw][v] = 0.f; dp[qw][v] = 0.f; }
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+    const bf16x8_t kf = lds_read_b128(ln.k_nat[ks] + off);
+    const bf16x8_t vf = lds_read_b128(ln.k_nat[ks] + off + ln.v_minus_k);
+#pragma unroll
+    for (int qw = 0; qw < QW; ++qw) {
+      s[qw] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qw][ks], s[qw], 0, 0, 0);
+      dp[qw] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, dof[qw][ks], dp[qw], 0, 0, 0);
+    }
+  }
+}
+
+// dQ^T += K^T dS^T for one 32-key half
+template <int QW>
+__device__ __forceinline__ void dq_accumulate(const DqLane& ln, unsigned off, const bf16x8_t (&dsf)[QW][2],
+                                              floatx16_t (&dq)[QW][4]) {
+#pragma unroll
+  for (int kstep = 0; kstep < 2; ++kstep)
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) {
+      const bf16x8_t a = concat_tr(lds_read_tr16_addr(ln.k_tr[dt][0] + off + kstep * 16 * 256),
+                                   lds_read_tr16_addr(ln.k_tr[dt][1] + off + kstep * 16 * 256));
+#pragma unroll
+      for (int qw = 0; qw < QW; ++qw)
+        dq[qw][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, dsf[qw][kstep], dq[qw][dt], 0, 0, 0);
+    }
+}
+
+// One 64-key tile in four phases, so that the vector work of one half overlaps the matrix
+// work of the other: scores(A) | scores(B) + softmax(A) | dQ(A) + softmax(B) | dQ(B).
+template <int QW, bool MASK>
+__device__ __forceinline__ void dq_tile(const DqLane& ln, unsigned off, const bf16x8_t (&qf)[QW][8],
+                                        const bf16x8_t (&dof)[QW][8], const float (&lse2)[QW],
+                                        const float (&dlt)[QW], floatx16_t (&dq)[QW][4], float c, int h,
+                                        int left) {
+  floatx16_t s_a[QW], dp_a[QW], s_b[QW], dp_b[QW];
+  bf16x8_t dsf_a[QW][2], dsf_b[QW][2], unused[2];
+  dq_scores<QW>(ln, off, qf, dof, s_a, dp_a);
+  __builtin_amdgcn_sched_barrier(0);
+  dq_scores<QW>(ln, off + 8192, qf, dof, s_b, dp_b);
+#pragma unroll
+  for (int qw = 0; qw < QW; ++qw)
+    softmax_bwd_regs<MASK, false>(s_a[qw], dp_a[qw], &lse2[qw], &dlt[qw], 0, c, h, left, unused, dsf_a[qw]);
+  __builtin_amdgcn_sched_barrier(0);
+  dq_accumulate<QW>(ln, off, dsf_a, dq);
+#pragma unroll
+  for (int qw = 0; qw < QW; ++qw)
+    softmax_bwd_regs<MASK, false>(s_b[qw], dp_b[qw], &lse2[qw], &dlt[qw], 0, c, h, left - 32, unused, dsf_b[qw]);
+  __builtin_amdgcn_sched_barrier(0);
+  dq_accumulate<QW>(ln, off + 8192, dsf_b, dq);
+}
+
+template <int NW, int QW>
+__global__ __launch_bounds__(NW * 64) void attn_bwd_dq_pipe_kernel(
+    const unsigned short* __restrict__ d_oh, const unsigned short* __restrict__ qh,
+    const unsigned short* __restrict__ kh, const unsigned short* __restrict__ vh,
+    const float* __restrict__ lse2, const float* __restrict__ delta,
+    const int32_t* __restrict__ cu_seqlens, int M, int64_t N, int H, float scale,
+    int tiles_per_head, unsigned short* __restrict__ d_qh) {
+  constexpr int BM = NW * 32 * QW;
+  constexpr int kDmaPerTile = 2 * (16 / NW);
+  __shared__ __attribute__((aligned(1024))) unsigned short Ks[kPipeNBuf][64 * kHeadDim];
+  __shared__ __attribute__((aligned(1024))) unsigned short Vs[kPipeNBuf][64 * kHeadDim];
+  __shared__ int s_start[MOGA_MAX_GROUPS + 1];
+  __shared__ int s_found;
+
+  const int64_t total = (int64_t)H * tiles_per_head;
+  const int64_t work = xcd_work_index(blockIdx.x, total);
+  if (work >= total) return;
+  const int head = (int)(work / tiles_per_head);
+  const int tile = (int)(work - (int64_t)head * tiles_per_head);
+  TileInfo ti;
+  if (!find_tile(cu_seqlens, M, BM, tile, s_start, &s_found, ti)) return;
+  const int gs = ti.row_begin, ge = ti.row_end, q0 = ti.tile_row;
+  const int n = ge - gs;
+
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int r = lane & 31, h = lane >> 5;
+  const int64_t head_off = (int64_t)head * N;
+  const float c = scale * 1.4426950408889634f;
+
+  bf16x8_t qf[QW][8], dof[QW][8];
+  float lq[QW], dl[QW];
+#pragma unroll
+  for (int qw = 0; qw < QW; ++qw) {
+    int qrow = q0 + (wave * QW + qw) * 32 + r;
+    if (qrow > ge - 1) qrow = ge - 1;
+    const unsigned short* qp = qh + (head_off + qrow) * kHeadDim + 8 * h;
+    const unsigned short* dp = d_oh + (head_off + qrow) * kHeadDim + 8 * h;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      qf[qw][ks] = *(const bf16x8_t*)(qp + 16 * ks);
+      dof[qw][ks] = *(const bf16x8_t*)(dp + 16 * ks);
+    }
+    lq[qw] = lse2[head_off + qrow];
+    dl[qw] = delta[head_off + qrow];
+  }
+
+  PipeDma dma;
+  dma.kbase = uniform_ptr(kh + (head_off + gs) * kHeadDim);
+  dma.vbase = uniform_ptr(vh + (head_off + gs) * kHeadDim);
+  dma.lds_k = lds_addr_uniform(&Ks[0][0]) + wave * 1024;
+  dma.lds_v = lds_addr_uniform(&Vs[0][0]) + wave * 1024;
+  dma.row0 = 4 * wave + (lane >> 4);
+  dma.chunk_off = (unsigned)(((lane & 15) ^ lds_swizzle(dma.row0)) * 16);
+  dma.last_row = n - 1;
+#pragma unroll
+  for (int t = 0; t <= kPipeAhead; ++t) pipe_issue_tile<NW>(dma, 64 * t, t);
+
+  DqLane ln;
+  {
+    const int krow_a = swap_bits_2_3(r);
+    const int k_sw = lds_swizzle(krow_a);
+    const unsigned kb = (unsigned)(uintptr_t)&Ks[0][0];
+    ln.v_minus_k = (unsigned)(uintptr_t)&Vs[0][0] - kb;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) ln.k_nat[ks] = kb + krow_a * 256 + (((2 * ks + h) ^ k_sw) << 4);
+    const int tr_r = 8 * h + ((lane & 15) >> 2);
+    const int tr_c = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
+    const int tr_e = 4 * (lane & 1);
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) {
+      ln.k_tr[dt][0] = kb + tr_e * 2 + tr_r * 256 + (((4 * dt + tr_c) ^ lds_swizzle(tr_r)) << 4);
+      ln.k_tr[dt][1] = kb + tr_e * 2 + (tr_r + 4) * 256 + (((4 * dt + tr_c) ^ lds_swizzle(tr_r + 4)) << 4);
+    }
+  }
+
+  floatx16_t dq[QW][4];
+#pragma unroll
+  for (int qw = 0; qw < QW; ++qw)
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) dq[qw][dt][v] = 0.f;
+
+  // tile T lives in ring slot T % 4; at the top of tile T the block waits for it, and refills the
+  // slot of tile T-1 (which every wave has left) with tile T+3
+  const int nfull = n >> 6;   // tiles whose 64 keys are all inside the group
+  int T = 0;
+  for (; T < nfull; ++T) {
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * kPipeAhead));
+    __syncthreads();
+    pipe_issue_tile<NW>(dma, 64 * (T + 1 + kPipeAhead), (T + 1 + kPipeAhead) & 3);
+    dq_tile<QW, false>(ln, ((unsigned)T & 3u) * kPipeTileBytes, qf, dof, lq, dl, dq, c, h, 64);
+  }
+  if (n & 63) {   // last, partial tile: masked keys contribute zero
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * kPipeAhead));
+    __syncthreads();
+    dq_tile<QW, true>(ln, ((unsigned)T & 3u) * kPipeTileBytes, qf, dof, lq, dl, dq, c, h, n - 64 * T);
+  }
+
+  __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // drain the look-ahead loads before the LDS is released
+#pragma unroll
+  for (int qw = 0; qw < QW; ++qw) {
+    const int qrow = q0 + (wave * QW + qw) * 32 + r;
+    if (qrow < ge) {
+      unsigned short* op = d_qh + (head_off + qrow) * kHeadDim + 4 * h;
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+          uintx2_t pk = {pack_bf16x2(dq[qw][dt][4 * b] * scale, dq[qw][dt][4 * b + 1] * scale),
+                         pack_bf16x2(dq[qw][dt][4 * b + 2] * scale, dq[qw][dt][4 * b + 3] * scale)};
+          *(uintx2_t*)(op + 32 * dt + 8 * b) = pk;
+        }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// dK, dV: key-stationary
+// ---------------------------------------------------------------------------------------
+struct DkvLane {
+  unsigned q_nat[8];     // Q fragment (row = permuted lane row), slot 0, half 0
+  unsigned q_tr[4][2];   // transposed Q read for d tile dt, rows +0 / +4
+  unsigned do_minus_q;   // LDS distance from the Q ring to the dO ring
+  unsigned lse_addr;     // lse2 of the lane's first row (8*h) in slot 0, half 0; delta is +delta_minus_lse
+  unsigned delta_minus_lse;
+};
+
+struct DkvFrags {
+  bf16x8_t qn[8], dn[8];   // Q, dO rows (A operands of S and dP)
+};
+struct DkvTrFrags {
+  bf16x8_t qtr[2][4], dtr[2][4];   // Q^T, dO^T (A operands of dK^T and dV^T)
+  float l2[16], dl[16];            // lse2 / delta of the lane's 16 query rows
+};
+
+__device__ __forceinline__ void dkdv_load_nat(const DkvLane& ln, unsigned off, DkvFrags& f) {
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+    f.qn[ks] = lds_read_b128(ln.q_nat[ks] + off);
+    f.dn[ks] = lds_read_b128(ln.q_nat[ks] + off + ln.do_minus_q);
+  }
+}
+
+__device__ __forceinline__ void dkdv_load_tr(const DkvLane& ln, unsigned off, unsigned off_row, DkvTrFrags& f) {
+  // register v of a score tile is query row 16*(v/8) + 8*h + v%8 of the step
+#pragma unroll
+  for (int kstep = 0; kstep < 2; ++kstep)
+#pragma unroll
+    for (int half4 = 0; half4 < 2; ++half4) {
+      const unsigned a = ln.lse_addr + off_row + (16 * kstep + 4 * half4) * 4;
+      const floatx4_t lv = lds_read_f32x4(a), dv4 = lds_read_f32x4(a + ln.delta_minus_lse);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { f.l2[8 * kstep + 4 * half4 + e] = lv[e]; f.dl[8 * kstep + 4 * half4 + e] = dv4[e]; }
+    }
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt) {
+    const unsigned a0 = ln.q_tr[dt][0] + off, a1 = ln.q_tr[dt][1] + off;
+#pragma unroll
+    for (int kstep = 0; kstep < 2; ++kstep) {
+      f.qtr[kstep][dt] = concat_tr(lds_read_tr16_addr(a0 + kstep * 16 * 256), lds_read_tr16_addr(a1 + kstep * 16 * 256));
+      f.dtr[kstep][dt] = concat_tr(lds_read_tr16_addr(a0 + ln.do_minus_q + kstep * 16 * 256),
+                                   lds_read_tr16_addr(a1 + ln.do_minus_q + kstep * 16 * 256));
+    }
+  }
+}
+
+__device__ __forceinline__ void dkdv_scores(const DkvFrags& f, const bf16x8_t (&kf)[8], const bf16x8_t (&vf)[8],
+                                            floatx16_t& s, floatx16_t& dp) {
+#pragma unroll
+  for (int v = 0; v < 16; ++v) { s[v] = 0.f; dp[v] = 0.f; }
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.qn[ks], kf[ks], s, 0, 0, 0);
+    dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.dn[ks], vf[ks], dp, 0, 0, 0);
+  }
+}
+
+__device__ __forceinline__ void dkdv_accumulate(const DkvTrFrags& f, const bf16x8_t (&pf)[2], const bf16x8_t (&dsf)[2],
+                                                floatx16_t (&dk)[4], floatx16_t (&dv)[4]) {
+#pragma unroll
+  for (int kstep = 0; kstep < 2; ++kstep)
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) {
+      dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.dtr[kstep][dt], pf[kstep], dv[dt], 0, 0, 0);
+      dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.qtr[kstep][dt], dsf[kstep], dk[dt], 0, 0, 0);
+    }
+}
+
+// One 64-query tile.  Order of the phases (A, B = first / second 32 queries):
+//   read rows(A) | S,dP(A) ; read rows(B), transposed(A) | S,dP(B) + softmax(A) |
+//   dV,dK(A) + softmax(B) ; read transposed(B) | dV,dK(B)
+template <bool MASK>
+__device__ __forceinline__ void dkdv_tile(const DkvLane& ln, unsigned off, unsigned off_row,
+                                          const bf16x8_t (&kf)[8], const bf16x8_t (&vf)[8],
+                                          floatx16_t (&dk)[4], floatx16_t (&dv)[4], float c, int h, int left) {
+  DkvFrags nat;
+  DkvTrFrags tr_a, tr_b;
+  floatx16_t s_a, dp_a, s_b, dp_b;
+  bf16x8_t pf_a[2], dsf_a[2], pf_b[2], dsf_b[2];
+  dkdv_load_nat(ln, off, nat);
+  __builtin_amdgcn_sched_barrier(0);
+  dkdv_scores(nat, kf, vf, s_a, dp_a);
+  __builtin_amdgcn_sched_barrier(0);
+  dkdv_load_nat(ln, off + 8192, nat);
+  dkdv_load_tr(ln, off, off_row, tr_a);
+  __builtin_amdgcn_sched_barrier(0);
+  dkdv_scores(nat, kf, vf, s_b, dp_b);
+  softmax_bwd_regs<MASK, true>(s_a, dp_a, tr_a.l2, tr_a.dl, 1, c, h, left, pf_a, dsf_a);
+  __builtin_amdgcn_sched_barrier(0);
+  dkdv_load_tr(ln, off + 8192, off_row + 128, tr_b);
+  dkdv_accumulate(tr_a, pf_a, dsf_a, dk, dv);
+  softmax_bwd_regs<MASK, true>(s_b, dp_b, tr_b.l2, tr_b.dl, 1, c, h, left - 32, pf_b, dsf_b);
+  __builtin_amdgcn_sched_barrier(0);
+  dkdv_accumulate(tr_b, pf_b, dsf_b, dk, dv);
+}
+
+template <int NW>
+__global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_pipe_kernel(
+    const unsigned short* __restrict__ d_oh, const unsigned short* __restrict__ qh,
+    const unsigned short* __restrict__ kh, const unsigned short* __restrict__ vh,
+    const float* __restrict__ lse2, const float* __restrict__ delta,
+    const int32_t* __restrict__ cu_seqlens, int M, int64_t N, int H, float scale,
+    int tiles_per_head, unsigned short* __restrict__ d_kh, unsigned short* __restrict__ d_vh) {
+  constexpr int BK = NW * 32;
+  constexpr int kDmaPerTile = 2 * (16 / NW) + 2;
+  __shared__ __attribute__((aligned(1024))) unsigned short Qs[kPipeNBuf][64 * kHeadDim];
+  __shared__ __attribute__((aligned(1024))) unsigned short dOs[kPipeNBuf][64 * kHeadDim];
+  __shared__ __attribute__((aligned(256))) float Ls[kPipeNBuf][64];   // lse * log2(e)
+  __shared__ __attribute__((aligned(256))) float Ds[kPipeNBuf][64];   // delta
+  __shared__ int s_start[MOGA_MAX_GROUPS + 1];
+  __shared__ int s_found;
+
+  const int64_t total = (int64_t)H * tiles_per_head;
+  const int64_t work = xcd_work_index(blockIdx.x, total);
+  if (work >= total) return;
+  const int head = (int)(work / tiles_per_head);
+  const int tile = (int)(work - (int64_t)head * tiles_per_head);
+  TileInfo ti;
+  if (!find_tile(cu_seqlens, M, BK, tile, s_start, &s_found, ti)) return;
+  const int gs = ti.row_begin, ge = ti.row_end, k0 = ti.tile_row;
+  const int n = ge - gs;
+
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int r = lane & 31, h = lane >> 5;
+  const int64_t head_off = (int64_t)head * N;
+  const float c = scale * 1.4426950408889634f;
+
+  // K, V fragments of this wave's 32 key rows: B operand, lane (r, h) holds row r, d = 16*ks + 8*h + 0..7
+  const int krow = k0 + wave * 32 + r;
+  const int krow_c = krow < ge ? krow : ge - 1;
+  bf16x8_t kf[8], vf[8];
+  {
+    const unsigned short* kp = kh + (head_off + krow_c) * kHeadDim + 8 * h;
+    const unsigned short* vp = vh + (head_off + krow_c) * kHeadDim + 8 * h;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      kf[ks] = *(const bf16x8_t*)(kp + 16 * ks);
+      vf[ks] = *(const bf16x8_t*)(vp + 16 * ks);
+    }
+  }
+
+  PipeDma dma;   // "k" = Q rows, "v" = dO rows of this head's group
+  dma.kbase = uniform_ptr(qh + (head_off + gs) * kHeadDim);
+  dma.vbase = uniform_ptr(d_oh + (head_off + gs) * kHeadDim);
+  dma.lds_k = lds_addr_uniform(&Qs[0][0]) + wave * 1024;
+  dma.lds_v = lds_addr_uniform(&dOs[0][0]) + wave * 1024;
+  dma.row0 = 4 * wave + (lane >> 4);
+  dma.chunk_off = (unsigned)(((lane & 15) ^ lds_swizzle(dma.row0)) * 16);
+  dma.last_row = n - 1;
+  const void* lbase = uniform_ptr(lse2 + head_off + gs);
+  const void* dbase = uniform_ptr(delta + head_off + gs);
+  const unsigned lds_l = lds_addr_uniform(&Ls[0][0]), lds_d = lds_addr_uniform(&Ds[0][0]);
+  // every wave issues the (identical) 64-float lse / delta loads so that all waves count alike
+  auto issue_tile = [&](int T) {
+    const int slot = T & 3;
+    pipe_issue_tile<NW>(dma, 64 * T, slot);
+    const unsigned roff = (unsigned)min(64 * T + lane, n - 1) * 4u;
+    lds_dma4_soff(lbase, roff, lds_l + slot * 256);
+    lds_dma4_soff(dbase, roff, lds_d + slot * 256);
+  };
+#pragma unroll
+  for (int t = 0; t <= kPipeAhead; ++t) issue_tile(t);
+
+  DkvLane ln;
+  {
+    const int qrow_a = swap_bits_2_3(r);
+    const int q_sw = lds_swizzle(qrow_a);
+    const unsigned qb = (unsigned)(uintptr_t)&Qs[0][0];
+    ln.do_minus_q = (unsigned)(uintptr_t)&dOs[0][0] - qb;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) ln.q_nat[ks] = qb + qrow_a * 256 + (((2 * ks + h) ^ q_sw) << 4);
+    const int tr_r = 8 * h + ((lane & 15) >> 2);
+    const int tr_c = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
+    const int tr_e = 4 * (lane & 1);
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) {
+      ln.q_tr[dt][0] = qb + tr_e * 2 + tr_r * 256 + (((4 * dt + tr_c) ^ lds_swizzle(tr_r)) << 4);
+      ln.q_tr[dt][1] = qb + tr_e * 2 + (tr_r + 4) * 256 + (((4 * dt + tr_c) ^ lds_swizzle(tr_r + 4)) << 4);
+    }
+    ln.lse_addr = (unsigned)(uintptr_t)&Ls[0][0] + 8 * h * 4;
+    ln.delta_minus_lse = (unsigned)(uintptr_t)&Ds[0][0] - (unsigned)(uintptr_t)&Ls[0][0];
+  }
+
+  floatx16_t dk[4], dv[4];
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { dk[dt][v] = 0.f; dv[dt][v] = 0.f; }
+
+  const int nfull = n >> 6;   // tiles whose 64 queries are all inside the group
+  int T = 0;
+  for (; T < nfull; ++T) {
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * kPipeAhead));
+    __syncthreads();
+    issue_tile(T + 1 + kPipeAhead);
+    dkdv_tile<false>(ln, ((unsigned)T & 3u) * kPipeTileBytes, ((unsigned)T & 3u) * 256, kf, vf, dk, dv, c, h, 64);
+  }
+  if (n & 63) {   // last, partial tile: masked queries contribute zero
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * kPipeAhead));
+    __syncthreads();
+    dkdv_tile<true>(ln, ((unsigned)T & 3u) * kPipeTileBytes, ((unsigned)T & 3u) * 256, kf, vf, dk, dv, c, h,
+                    n - 64 * T);
+  }
+
+  __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // drain the look-ahead loads before the LDS is released
+  if (krow < ge) {
+    unsigned short* dkp = d_kh + (head_off + krow) * kHeadDim + 4 * h;
+    unsigned short* dvp = d_vh + (head_off + krow) * kHeadDim + 4 * h;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        uintx2_t pk = {pack_bf16x2(dk[dt][4 * b] * scale, dk[dt][4 * b + 1] * scale),
+                       pack_bf16x2(dk[dt][4 * b + 2] * scale, dk[dt][4 * b + 3] * scale)};
+        uintx2_t pv = {pack_bf16x2(dv[dt][4 * b], dv[dt][4 * b + 1]),
+                       pack_bf16x2(dv[dt][4 * b + 2], dv[dt][4 * b + 3])};
+        *(uintx2_t*)(dkp + 32 * dt + 8 * b) = pk;
+        *(uintx2_t*)(dvp + 32 * dt + 8 * b) = pv;
+      }
+  }
+}
+
+}  // namespace moga

@@ -81,6 +81,7 @@ def attn_bwd_case(sizes, H, D, dtype, seed):
     ([300, 0, 1, 129, 257, 64, 2, 511], 3, 128, "bf16"),
     ([2049, 1500, 17], 2, 128, "bf16"),
     ([40], 1, 128, "bf16"),
+    ([288, 289, 319, 320, 321, 352, 33, 32, 31, 63, 64, 65, 95, 96, 97, 127, 128, 129, 255, 256, 257, 1, 2], 1, 128, "bf16"),
 ])
 def test_group_attention_backward_matches_oracle(sizes, H, D, dtype):
     say(f"attn bwd sizes={sizes} H={H} D={D} {dtype}")

@@ -151,6 +151,7 @@ def attn_case(sizes, H, D, dtype, seed, scale=None, peaked=False):
     ([300, 0, 1, 129, 257, 64, 2, 511], 3, 128, "bf16"),  # crosses 64/128/256 tile edges
     ([4095, 4096, 17], 2, 128, "bf16"),
     ([40], 1, 128, "bf16"),
+    ([288, 289, 319, 320, 321, 352, 575, 576, 577, 33, 32, 31, 63, 64, 65, 95, 96, 97, 127, 128, 1, 2], 1, 128, "bf16"),
 ])
 def test_group_attention_forward_matches_oracle(sizes, H, D, dtype):
     say(f"attn fwd sizes={sizes} H={H} D={D} {dtype}")
