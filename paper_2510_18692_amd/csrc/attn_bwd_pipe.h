@@ -26,35 +26,56 @@ __device__ __forceinline__ floatx4_t lds_read_f32x4(unsigned addr) {
   return *(const floatx4_t __attribute__((address_space(3)))*)(uintptr_t)addr;
 }
 
-// exp2(s*c - lse2) and dS = P * (dP - delta) for the 16 scores of a lane, packed to bf16.
-// `limit`: contraction indices >= limit (relative to the step's first) get P = 0 (MASK only).
-// lse2 / dlt are per register (PER_REG: 16 values, the lane's 16 rows) or one per lane.
-template <bool MASK, bool WANT_P>
-__device__ __forceinline__ void softmax_bwd_regs(const floatx16_t& s, const floatx16_t& dp,
-                                                 const float* lse2, const float* dlt, int stride,
-                                                 float c, int h, int limit, bf16x8_t (&pf)[2],
-                                                 bf16x8_t (&dsf)[2]) {
+// dQ kernel: P = exp2(s*c - lse2) and dS = P * (dP - delta) for the 16 scores of a lane (one query
+// column per lane, so lse2 and delta are per-lane scalars), dS packed to bf16.
+// `limit`: keys >= limit (relative to the step's first) get P = 0 (MASK only).
+template <bool MASK>
+__device__ __forceinline__ void softmax_bwd_cols(const floatx16_t& s, const floatx16_t& dp, float lse2,
+                                                 float dlt, float c, int h, int limit, bf16x8_t (&dsf)[2]) {
+#pragma unroll
+  for (int kstep = 0; kstep < 2; ++kstep) {
+    unsigned int dd[4];
+#pragma unroll
+    for (int j = 0; j < 8; j += 2) {
+      const int v = 8 * kstep + j;
+      float pa = fast_exp2(fmaf(s[v], c, -lse2));
+      float pb = fast_exp2(fmaf(s[v + 1], c, -lse2));
+      if (MASK) {
+        const int idx = 16 * kstep + 8 * h + j;
+        if (idx >= limit) pa = 0.f;
+        if (idx + 1 >= limit) pb = 0.f;
+      }
+      dd[j >> 1] = pack_bf16x2(pa * (dp[v] - dlt), pb * (dp[v + 1] - dlt));
+    }
+    const uintx4_t du = {dd[0], dd[1], dd[2], dd[3]};
+    dsf[kstep] = __builtin_bit_cast(bf16x8_t, du);
+  }
+}
+
+// dK/dV kernel: the score accumulators were started from -lse/scale and -delta of their rows, so
+// s already holds S - lse/scale and dp holds dP - delta: P = exp2(c*s), dS = P * dp.
+// `limit`: query rows >= limit (relative to the step's first) get P = 0 (MASK only).
+template <bool MASK>
+__device__ __forceinline__ void softmax_bwd_rows(const floatx16_t& s, const floatx16_t& dp, float c, int h,
+                                                 int limit, bf16x8_t (&pf)[2], bf16x8_t (&dsf)[2]) {
 #pragma unroll
   for (int kstep = 0; kstep < 2; ++kstep) {
     unsigned int pp[4], dd[4];
 #pragma unroll
     for (int j = 0; j < 8; j += 2) {
       const int v = 8 * kstep + j;
-      float pa = fast_exp2(fmaf(s[v], c, -lse2[v * stride]));
-      float pb = fast_exp2(fmaf(s[v + 1], c, -lse2[(v + 1) * stride]));
+      float pa = fast_exp2(s[v] * c);
+      float pb = fast_exp2(s[v + 1] * c);
       if (MASK) {
         const int idx = 16 * kstep + 8 * h + j;
         if (idx >= limit) pa = 0.f;
         if (idx + 1 >= limit) pb = 0.f;
       }
-      if (WANT_P) pp[j >> 1] = pack_bf16x2(pa, pb);
-      dd[j >> 1] = pack_bf16x2(pa * (dp[v] - dlt[v * stride]), pb * (dp[v + 1] - dlt[(v + 1) * stride]));
+      pp[j >> 1] = pack_bf16x2(pa, pb);
+      dd[j >> 1] = pack_bf16x2(pa * dp[v], pb * dp[v + 1]);
     }
-    if (WANT_P) {
-      const uintx4_t pu = {pp[0], pp[1], pp[2], pp[3]};
-      pf[kstep] = __builtin_bit_cast(bf16x8_t, pu);
-    }
-    const uintx4_t du = {dd[0], dd[1], dd[2], dd[3]};
+    const uintx4_t pu = {pp[0], pp[1], pp[2], pp[3]}, du = {dd[0], dd[1], dd[2], dd[3]};
+    pf[kstep] = __builtin_bit_cast(bf16x8_t, pu);
     dsf[kstep] = __builtin_bit_cast(bf16x8_t, du);
   }
 }
@@ -64,12 +85,12 @@ __device__ __forceinline__ void softmax_bwd_regs(const floatx16_t& s, const floa
 // ---------------------------------------------------------------------------------------
 struct DqLane {
   unsigned k_nat[8];     // K fragment (row = permuted lane row) for d chunk pair ks, slot 0, half 0
+  unsigned v_nat[8];     // same for V
   unsigned k_tr[4][2];   // transposed K read for d tile dt, rows +0 / +4
-  unsigned v_minus_k;    // LDS distance from the K ring to the V ring
 };
 
 // S^T = K Q^T and dP^T = V dO^T for one 32-key half of a tile
-template <int QW>
+template <int QW, int SOFF>
 __device__ __forceinline__ void dq_scores(const DqLane& ln, unsigned off, const bf16x8_t (&qf)[QW][8],
                                           const bf16x8_t (&dof)[QW][8], floatx16_t (&s)[QW],
                                           floatx16_t (&dp)[QW]) {
@@ -79,8 +100,8 @@ __device__ __forceinline__ void dq_scores(const DqLane& ln, unsigned off, const 
     for (int v = 0; v < 16; ++v) { s[qw][v] = 0.f; dp[qw][v] = 0.f; }
 #pragma unroll
   for (int ks = 0; ks < 8; ++ks) {
-    const bf16x8_t kf = lds_read_b128(ln.k_nat[ks] + off);
-    const bf16x8_t vf = lds_read_b128(ln.k_nat[ks] + off + ln.v_minus_k);
+    const bf16x8_t kf = lds_read_b128(ln.k_nat[ks] + off + SOFF);
+    const bf16x8_t vf = lds_read_b128(ln.v_nat[ks] + off + SOFF);
 #pragma unroll
     for (int qw = 0; qw < QW; ++qw) {
       s[qw] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qw][ks], s[qw], 0, 0, 0);
@@ -90,15 +111,15 @@ __device__ __forceinline__ void dq_scores(const DqLane& ln, unsigned off, const 
 }
 
 // dQ^T += K^T dS^T for one 32-key half
-template <int QW>
+template <int QW, int SOFF>
 __device__ __forceinline__ void dq_accumulate(const DqLane& ln, unsigned off, const bf16x8_t (&dsf)[QW][2],
                                               floatx16_t (&dq)[QW][4]) {
 #pragma unroll
   for (int kstep = 0; kstep < 2; ++kstep)
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt) {
-      const bf16x8_t a = concat_tr(lds_read_tr16_addr(ln.k_tr[dt][0] + off + kstep * 16 * 256),
-                                   lds_read_tr16_addr(ln.k_tr[dt][1] + off + kstep * 16 * 256));
+      const bf16x8_t a = concat_tr(lds_read_tr16_addr(ln.k_tr[dt][0] + off + SOFF + kstep * 16 * 256),
+                                   lds_read_tr16_addr(ln.k_tr[dt][1] + off + SOFF + kstep * 16 * 256));
 #pragma unroll
       for (int qw = 0; qw < QW; ++qw)
         dq[qw][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, dsf[qw][kstep], dq[qw][dt], 0, 0, 0);
@@ -107,33 +128,33 @@ __device__ __forceinline__ void dq_accumulate(const DqLane& ln, unsigned off, co
 
 // One 64-key tile in four phases, so that the vector work of one half overlaps the matrix
 // work of the other: scores(A) | scores(B) + softmax(A) | dQ(A) + softmax(B) | dQ(B).
-template <int QW, bool MASK>
+template <int QW, bool MASK, int SOFF>
 __device__ __forceinline__ void dq_tile(const DqLane& ln, unsigned off, const bf16x8_t (&qf)[QW][8],
                                         const bf16x8_t (&dof)[QW][8], const float (&lse2)[QW],
                                         const float (&dlt)[QW], floatx16_t (&dq)[QW][4], float c, int h,
                                         int left) {
   floatx16_t s_a[QW], dp_a[QW], s_b[QW], dp_b[QW];
-  bf16x8_t dsf_a[QW][2], dsf_b[QW][2], unused[2];
-  dq_scores<QW>(ln, off, qf, dof, s_a, dp_a);
+  bf16x8_t dsf_a[QW][2], dsf_b[QW][2];
+  dq_scores<QW, SOFF>(ln, off, qf, dof, s_a, dp_a);
   __builtin_amdgcn_sched_barrier(0);
-  dq_scores<QW>(ln, off + 8192, qf, dof, s_b, dp_b);
+  dq_scores<QW, SOFF + 8192>(ln, off, qf, dof, s_b, dp_b);
 #pragma unroll
   for (int qw = 0; qw < QW; ++qw)
-    softmax_bwd_regs<MASK, false>(s_a[qw], dp_a[qw], &lse2[qw], &dlt[qw], 0, c, h, left, unused, dsf_a[qw]);
+    softmax_bwd_cols<MASK>(s_a[qw], dp_a[qw], lse2[qw], dlt[qw], c, h, left, dsf_a[qw]);
   __builtin_amdgcn_sched_barrier(0);
-  dq_accumulate<QW>(ln, off, dsf_a, dq);
+  dq_accumulate<QW, SOFF>(ln, off, dsf_a, dq);
 #pragma unroll
   for (int qw = 0; qw < QW; ++qw)
-    softmax_bwd_regs<MASK, false>(s_b[qw], dp_b[qw], &lse2[qw], &dlt[qw], 0, c, h, left - 32, unused, dsf_b[qw]);
+    softmax_bwd_cols<MASK>(s_b[qw], dp_b[qw], lse2[qw], dlt[qw], c, h, left - 32, dsf_b[qw]);
   __builtin_amdgcn_sched_barrier(0);
-  dq_accumulate<QW>(ln, off + 8192, dsf_b, dq);
+  dq_accumulate<QW, SOFF + 8192>(ln, off, dsf_b, dq);
 }
 
 template <int NW, int QW>
 __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_pipe_kernel(
     const unsigned short* __restrict__ d_oh, const unsigned short* __restrict__ qh,
     const unsigned short* __restrict__ kh, const unsigned short* __restrict__ vh,
-    const float* __restrict__ lse2, const float* __restrict__ delta,
+    const float* __restrict__ neg_lse_over_scale, const float* __restrict__ neg_delta,
     const int32_t* __restrict__ cu_seqlens, int M, int64_t N, int H, float scale,
     int tiles_per_head, unsigned short* __restrict__ d_qh) {
   constexpr int BM = NW * 32 * QW;
@@ -171,8 +192,8 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_pipe_kernel(
       qf[qw][ks] = *(const bf16x8_t*)(qp + 16 * ks);
       dof[qw][ks] = *(const bf16x8_t*)(dp + 16 * ks);
     }
-    lq[qw] = lse2[head_off + qrow];
-    dl[qw] = delta[head_off + qrow];
+    lq[qw] = -neg_lse_over_scale[head_off + qrow] * c;   // lse * log2(e)
+    dl[qw] = -neg_delta[head_off + qrow];
   }
 
   PipeDma dma;
@@ -191,9 +212,12 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_pipe_kernel(
     const int krow_a = swap_bits_2_3(r);
     const int k_sw = lds_swizzle(krow_a);
     const unsigned kb = (unsigned)(uintptr_t)&Ks[0][0];
-    ln.v_minus_k = (unsigned)(uintptr_t)&Vs[0][0] - kb;
+    const unsigned vb = (unsigned)(uintptr_t)&Vs[0][0];
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) ln.k_nat[ks] = kb + krow_a * 256 + (((2 * ks + h) ^ k_sw) << 4);
+    for (int ks = 0; ks < 8; ++ks) {
+      ln.k_nat[ks] = kb + krow_a * 256 + (((2 * ks + h) ^ k_sw) << 4);
+      ln.v_nat[ks] = vb + krow_a * 256 + (((2 * ks + h) ^ k_sw) << 4);
+    }
     const int tr_r = 8 * h + ((lane & 15) >> 2);
     const int tr_c = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
     const int tr_e = 4 * (lane & 1);
@@ -216,16 +240,28 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_pipe_kernel(
   // slot of tile T-1 (which every wave has left) with tile T+3
   const int nfull = n >> 6;   // tiles whose 64 keys are all inside the group
   int T = 0;
+#define MOGA_DQ_TILE(B)                                                                  \
+  __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * kPipeAhead));                      \
+  __syncthreads();                                                                       \
+  pipe_issue_tile<NW>(dma, 64 * (T + (B) + 1 + kPipeAhead), ((B) + 1 + kPipeAhead) & 3); \
+  dq_tile<QW, false, (B) * kPipeTileBytes>(ln, 0, qf, dof, lq, dl, dq, c, h, 64);
+  for (; T + 4 <= nfull; T += 4) {   // four tiles per iteration: every LDS offset is an immediate
+    MOGA_DQ_TILE(0)
+    MOGA_DQ_TILE(1)
+    MOGA_DQ_TILE(2)
+    MOGA_DQ_TILE(3)
+  }
+#undef MOGA_DQ_TILE
   for (; T < nfull; ++T) {
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * kPipeAhead));
     __syncthreads();
     pipe_issue_tile<NW>(dma, 64 * (T + 1 + kPipeAhead), (T + 1 + kPipeAhead) & 3);
-    dq_tile<QW, false>(ln, ((unsigned)T & 3u) * kPipeTileBytes, qf, dof, lq, dl, dq, c, h, 64);
+    dq_tile<QW, false, 0>(ln, ((unsigned)T & 3u) * kPipeTileBytes, qf, dof, lq, dl, dq, c, h, 64);
   }
   if (n & 63) {   // last, partial tile: masked keys contribute zero
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * kPipeAhead));
     __syncthreads();
-    dq_tile<QW, true>(ln, ((unsigned)T & 3u) * kPipeTileBytes, qf, dof, lq, dl, dq, c, h, n - 64 * T);
+    dq_tile<QW, true, 0>(ln, ((unsigned)T & 3u) * kPipeTileBytes, qf, dof, lq, dl, dq, c, h, n - 64 * T);
   }
 
   __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // drain the look-ahead loads before the LDS is released
@@ -250,11 +286,9 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_pipe_kernel(
 // dK, dV: key-stationary
 // ---------------------------------------------------------------------------------------
 struct DkvLane {
-  unsigned q_nat[8];     // Q fragment (row = permuted lane row), slot 0, half 0
-  unsigned q_tr[4][2];   // transposed Q read for d tile dt, rows +0 / +4
-  unsigned do_minus_q;   // LDS distance from the Q ring to the dO ring
-  unsigned lse_addr;     // lse2 of the lane's first row (8*h) in slot 0, half 0; delta is +delta_minus_lse
-  unsigned delta_minus_lse;
+  unsigned q_nat[8], do_nat[8];     // Q / dO fragment (row = permuted lane row), slot 0, half 0
+  unsigned q_tr[4][2], do_tr[4][2]; // transposed Q / dO read for d tile dt, rows +0 / +4
+  unsigned lse_addr, delta_addr;    // -lse/scale and -delta of the lane's first row (8*h), slot 0, half 0
 };
 
 struct DkvFrags {
@@ -262,44 +296,47 @@ struct DkvFrags {
 };
 struct DkvTrFrags {
   bf16x8_t qtr[2][4], dtr[2][4];   // Q^T, dO^T (A operands of dK^T and dV^T)
-  float l2[16], dl[16];            // lse2 / delta of the lane's 16 query rows
 };
 
+template <int SOFF>
 __device__ __forceinline__ void dkdv_load_nat(const DkvLane& ln, unsigned off, DkvFrags& f) {
 #pragma unroll
   for (int ks = 0; ks < 8; ++ks) {
-    f.qn[ks] = lds_read_b128(ln.q_nat[ks] + off);
-    f.dn[ks] = lds_read_b128(ln.q_nat[ks] + off + ln.do_minus_q);
+    f.qn[ks] = lds_read_b128(ln.q_nat[ks] + off + SOFF);
+    f.dn[ks] = lds_read_b128(ln.do_nat[ks] + off + SOFF);
   }
 }
 
-__device__ __forceinline__ void dkdv_load_tr(const DkvLane& ln, unsigned off, unsigned off_row, DkvTrFrags& f) {
-  // register v of a score tile is query row 16*(v/8) + 8*h + v%8 of the step
+// Start values of the score accumulators: register v of a score tile is query row
+// 16*(v/8) + 8*h + v%8 of the step; s starts at -lse/scale and dp at -delta of that row.
+template <int SROW>
+__device__ __forceinline__ void dkdv_load_init(const DkvLane& ln, unsigned off_row, floatx16_t& s, floatx16_t& dp) {
 #pragma unroll
   for (int kstep = 0; kstep < 2; ++kstep)
 #pragma unroll
     for (int half4 = 0; half4 < 2; ++half4) {
-      const unsigned a = ln.lse_addr + off_row + (16 * kstep + 4 * half4) * 4;
-      const floatx4_t lv = lds_read_f32x4(a), dv4 = lds_read_f32x4(a + ln.delta_minus_lse);
+      const unsigned o = off_row + SROW + (16 * kstep + 4 * half4) * 4;
+      const floatx4_t lv = lds_read_f32x4(ln.lse_addr + o), dv4 = lds_read_f32x4(ln.delta_addr + o);
 #pragma unroll
-      for (int e = 0; e < 4; ++e) { f.l2[8 * kstep + 4 * half4 + e] = lv[e]; f.dl[8 * kstep + 4 * half4 + e] = dv4[e]; }
+      for (int e = 0; e < 4; ++e) { s[8 * kstep + 4 * half4 + e] = lv[e]; dp[8 * kstep + 4 * half4 + e] = dv4[e]; }
     }
+}
+
+template <int SOFF>
+__device__ __forceinline__ void dkdv_load_tr(const DkvLane& ln, unsigned off, DkvTrFrags& f) {
 #pragma unroll
-  for (int dt = 0; dt < 4; ++dt) {
-    const unsigned a0 = ln.q_tr[dt][0] + off, a1 = ln.q_tr[dt][1] + off;
+  for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
     for (int kstep = 0; kstep < 2; ++kstep) {
-      f.qtr[kstep][dt] = concat_tr(lds_read_tr16_addr(a0 + kstep * 16 * 256), lds_read_tr16_addr(a1 + kstep * 16 * 256));
-      f.dtr[kstep][dt] = concat_tr(lds_read_tr16_addr(a0 + ln.do_minus_q + kstep * 16 * 256),
-                                   lds_read_tr16_addr(a1 + ln.do_minus_q + kstep * 16 * 256));
+      f.qtr[kstep][dt] = concat_tr(lds_read_tr16_addr(ln.q_tr[dt][0] + off + SOFF + kstep * 16 * 256),
+                                   lds_read_tr16_addr(ln.q_tr[dt][1] + off + SOFF + kstep * 16 * 256));
+      f.dtr[kstep][dt] = concat_tr(lds_read_tr16_addr(ln.do_tr[dt][0] + off + SOFF + kstep * 16 * 256),
+                                   lds_read_tr16_addr(ln.do_tr[dt][1] + off + SOFF + kstep * 16 * 256));
     }
-  }
 }
 
 __device__ __forceinline__ void dkdv_scores(const DkvFrags& f, const bf16x8_t (&kf)[8], const bf16x8_t (&vf)[8],
                                             floatx16_t& s, floatx16_t& dp) {
-#pragma unroll
-  for (int v = 0; v < 16; ++v) { s[v] = 0.f; dp[v] = 0.f; }
 #pragma unroll
   for (int ks = 0; ks < 8; ++ks) {
     s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.qn[ks], kf[ks], s, 0, 0, 0);
@@ -321,27 +358,29 @@ __device__ __forceinline__ void dkdv_accumulate(const DkvTrFrags& f, const bf16x
 // One 64-query tile.  Order of the phases (A, B = first / second 32 queries):
 //   read rows(A) | S,dP(A) ; read rows(B), transposed(A) | S,dP(B) + softmax(A) |
 //   dV,dK(A) + softmax(B) ; read transposed(B) | dV,dK(B)
-template <bool MASK>
+// SLOT: ring slot as a compile-time constant (then off / off_row are 0), or -1 for run-time offsets.
+template <bool MASK, int SOFF, int SROW>
 __device__ __forceinline__ void dkdv_tile(const DkvLane& ln, unsigned off, unsigned off_row,
                                           const bf16x8_t (&kf)[8], const bf16x8_t (&vf)[8],
                                           floatx16_t (&dk)[4], floatx16_t (&dv)[4], float c, int h, int left) {
-  DkvFrags nat;
+  DkvFrags nat_a, nat_b;
   DkvTrFrags tr_a, tr_b;
   floatx16_t s_a, dp_a, s_b, dp_b;
   bf16x8_t pf_a[2], dsf_a[2], pf_b[2], dsf_b[2];
-  dkdv_load_nat(ln, off, nat);
+  dkdv_load_nat<SOFF>(ln, off, nat_a);
+  dkdv_load_init<SROW>(ln, off_row, s_a, dp_a);
   __builtin_amdgcn_sched_barrier(0);
-  dkdv_scores(nat, kf, vf, s_a, dp_a);
+  dkdv_load_nat<SOFF + 8192>(ln, off, nat_b);        // in flight while S, dP of A are computed
+  dkdv_load_init<SROW + 128>(ln, off_row, s_b, dp_b);
+  dkdv_scores(nat_a, kf, vf, s_a, dp_a);
   __builtin_amdgcn_sched_barrier(0);
-  dkdv_load_nat(ln, off + 8192, nat);
-  dkdv_load_tr(ln, off, off_row, tr_a);
+  dkdv_load_tr<SOFF>(ln, off, tr_a);                 // in flight while S, dP of B are computed
+  dkdv_scores(nat_b, kf, vf, s_b, dp_b);
+  softmax_bwd_rows<MASK>(s_a, dp_a, c, h, left, pf_a, dsf_a);
   __builtin_amdgcn_sched_barrier(0);
-  dkdv_scores(nat, kf, vf, s_b, dp_b);
-  softmax_bwd_regs<MASK, true>(s_a, dp_a, tr_a.l2, tr_a.dl, 1, c, h, left, pf_a, dsf_a);
-  __builtin_amdgcn_sched_barrier(0);
-  dkdv_load_tr(ln, off + 8192, off_row + 128, tr_b);
+  dkdv_load_tr<SOFF + 8192>(ln, off, tr_b);          // in flight while dV, dK of A are accumulated
   dkdv_accumulate(tr_a, pf_a, dsf_a, dk, dv);
-  softmax_bwd_regs<MASK, true>(s_b, dp_b, tr_b.l2, tr_b.dl, 1, c, h, left - 32, pf_b, dsf_b);
+  softmax_bwd_rows<MASK>(s_b, dp_b, c, h, left - 32, pf_b, dsf_b);
   __builtin_amdgcn_sched_barrier(0);
   dkdv_accumulate(tr_b, pf_b, dsf_b, dk, dv);
 }
@@ -350,15 +389,15 @@ template <int NW>
 __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_pipe_kernel(
     const unsigned short* __restrict__ d_oh, const unsigned short* __restrict__ qh,
     const unsigned short* __restrict__ kh, const unsigned short* __restrict__ vh,
-    const float* __restrict__ lse2, const float* __restrict__ delta,
+    const float* __restrict__ neg_lse_over_scale, const float* __restrict__ neg_delta,
     const int32_t* __restrict__ cu_seqlens, int M, int64_t N, int H, float scale,
     int tiles_per_head, unsigned short* __restrict__ d_kh, unsigned short* __restrict__ d_vh) {
   constexpr int BK = NW * 32;
   constexpr int kDmaPerTile = 2 * (16 / NW) + 2;
   __shared__ __attribute__((aligned(1024))) unsigned short Qs[kPipeNBuf][64 * kHeadDim];
   __shared__ __attribute__((aligned(1024))) unsigned short dOs[kPipeNBuf][64 * kHeadDim];
-  __shared__ __attribute__((aligned(256))) float Ls[kPipeNBuf][64];   // lse * log2(e)
-  __shared__ __attribute__((aligned(256))) float Ds[kPipeNBuf][64];   // delta
+  __shared__ __attribute__((aligned(256))) float Ls[kPipeNBuf][64];   // -lse / scale
+  __shared__ __attribute__((aligned(256))) float Ds[kPipeNBuf][64];   // -delta
   __shared__ int s_start[MOGA_MAX_GROUPS + 1];
   __shared__ int s_found;
 
@@ -399,8 +438,8 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_pipe_kernel(
   dma.row0 = 4 * wave + (lane >> 4);
   dma.chunk_off = (unsigned)(((lane & 15) ^ lds_swizzle(dma.row0)) * 16);
   dma.last_row = n - 1;
-  const void* lbase = uniform_ptr(lse2 + head_off + gs);
-  const void* dbase = uniform_ptr(delta + head_off + gs);
+  const void* lbase = uniform_ptr(neg_lse_over_scale + head_off + gs);
+  const void* dbase = uniform_ptr(neg_delta + head_off + gs);
   const unsigned lds_l = lds_addr_uniform(&Ls[0][0]), lds_d = lds_addr_uniform(&Ds[0][0]);
   // every wave issues the (identical) 64-float lse / delta loads so that all waves count alike
   auto issue_tile = [&](int T) {
@@ -418,19 +457,26 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_pipe_kernel(
     const int qrow_a = swap_bits_2_3(r);
     const int q_sw = lds_swizzle(qrow_a);
     const unsigned qb = (unsigned)(uintptr_t)&Qs[0][0];
-    ln.do_minus_q = (unsigned)(uintptr_t)&dOs[0][0] - qb;
+    const unsigned db = (unsigned)(uintptr_t)&dOs[0][0];
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) ln.q_nat[ks] = qb + qrow_a * 256 + (((2 * ks + h) ^ q_sw) << 4);
+    for (int ks = 0; ks < 8; ++ks) {
+      ln.q_nat[ks] = qb + qrow_a * 256 + (((2 * ks + h) ^ q_sw) << 4);
+      ln.do_nat[ks] = db + qrow_a * 256 + (((2 * ks + h) ^ q_sw) << 4);
+    }
     const int tr_r = 8 * h + ((lane & 15) >> 2);
     const int tr_c = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
     const int tr_e = 4 * (lane & 1);
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt) {
-      ln.q_tr[dt][0] = qb + tr_e * 2 + tr_r * 256 + (((4 * dt + tr_c) ^ lds_swizzle(tr_r)) << 4);
-      ln.q_tr[dt][1] = qb + tr_e * 2 + (tr_r + 4) * 256 + (((4 * dt + tr_c) ^ lds_swizzle(tr_r + 4)) << 4);
+      const unsigned o0 = tr_e * 2 + tr_r * 256 + (((4 * dt + tr_c) ^ lds_swizzle(tr_r)) << 4);
+      const unsigned o1 = tr_e * 2 + (tr_r + 4) * 256 + (((4 * dt + tr_c) ^ lds_swizzle(tr_r + 4)) << 4);
+      ln.q_tr[dt][0] = qb + o0;
+      ln.q_tr[dt][1] = qb + o1;
+      ln.do_tr[dt][0] = db + o0;
+      ln.do_tr[dt][1] = db + o1;
     }
     ln.lse_addr = (unsigned)(uintptr_t)&Ls[0][0] + 8 * h * 4;
-    ln.delta_minus_lse = (unsigned)(uintptr_t)&Ds[0][0] - (unsigned)(uintptr_t)&Ls[0][0];
+    ln.delta_addr = (unsigned)(uintptr_t)&Ds[0][0] + 8 * h * 4;
   }
 
   floatx16_t dk[4], dv[4];
@@ -441,17 +487,29 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_pipe_kernel(
 
   const int nfull = n >> 6;   // tiles whose 64 queries are all inside the group
   int T = 0;
+#define MOGA_DKDV_TILE(B)                                                        \
+  __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * kPipeAhead));              \
+  __syncthreads();                                                               \
+  issue_tile(T + (B) + 1 + kPipeAhead);                                          \
+  dkdv_tile<false, (B) * kPipeTileBytes, (B) * 256>(ln, 0, 0, kf, vf, dk, dv, c, h, 64);
+  for (; T + 4 <= nfull; T += 4) {   // four tiles per iteration: every LDS offset is an immediate
+    MOGA_DKDV_TILE(0)
+    MOGA_DKDV_TILE(1)
+    MOGA_DKDV_TILE(2)
+    MOGA_DKDV_TILE(3)
+  }
+#undef MOGA_DKDV_TILE
   for (; T < nfull; ++T) {
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * kPipeAhead));
     __syncthreads();
     issue_tile(T + 1 + kPipeAhead);
-    dkdv_tile<false>(ln, ((unsigned)T & 3u) * kPipeTileBytes, ((unsigned)T & 3u) * 256, kf, vf, dk, dv, c, h, 64);
+    dkdv_tile<false, 0, 0>(ln, ((unsigned)T & 3u) * kPipeTileBytes, ((unsigned)T & 3u) * 256, kf, vf, dk, dv, c, h, 64);
   }
   if (n & 63) {   // last, partial tile: masked queries contribute zero
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * kPipeAhead));
     __syncthreads();
-    dkdv_tile<true>(ln, ((unsigned)T & 3u) * kPipeTileBytes, ((unsigned)T & 3u) * 256, kf, vf, dk, dv, c, h,
-                    n - 64 * T);
+    dkdv_tile<true, 0, 0>(ln, ((unsigned)T & 3u) * kPipeTileBytes, ((unsigned)T & 3u) * 256, kf, vf, dk, dv, c, h,
+                          n - 64 * T);
   }
 
   __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // drain the look-ahead loads before the LDS is released
