@@ -27,6 +27,15 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, published
 
+# HBM bytes per call, measured with two rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE; each scaled
+# by what the same counter reads for a plain 1 GiB copy: FETCH x 2.00, WRITE x 1.00).  Summary and
+# commands: profiles/layer_C4b_hbm_traffic.md.  Only the workload it was measured on has an entry.
+MEASURED_HBM_BYTES = {
+    ("C4b", "moga_route"): 6.10e9, ("C4b", "moga_permute"): 35.7e9, ("C4b", "moga_group_attn_fwd"): 49.8e9,
+    ("C4b", "moga_unpermute"): 11.9e9, ("C4b", "moga_unpermute_bwd"): 17.9e9,
+    ("C4b", "moga_group_attn_bwd"): 191.9e9, ("C4b", "moga_permute_bwd"): 35.7e9, ("C4b", "moga_route_bwd"): 6.76e9,
+}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -35,6 +44,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="C4b", help="C1, C1b, C2, C3, C3b, C4, C4b (default), C5")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (a kernel of known traffic, used to scale "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
 
 
@@ -156,6 +168,12 @@ def main():
             out["d_w"] = d_w
         return out
 
+    if args.calibrate_copy:
+        a = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
+        b = torch.empty_like(a)
+        b.copy_(a)          # 1 GiB read + 1 GiB written
+        torch.cuda.synchronize()
+        del a, b
     for _ in range(args.warmup):
         out = step()
         torch.cuda.synchronize()
@@ -191,7 +209,7 @@ def main():
     roof = {k: calls[dominant][k] for k in ("bound", "achieved", "peak", "unit", "frac")}
     roof["kernel"] = dominant
     roof["ms"] = calls[dominant]["ms"]
-    roof["traffic"] = None
+    roof["traffic"] = MEASURED_HBM_BYTES.get((w.name, dominant))
 
     from paper_2510_18692_amd import flops
     total_flops = flops.group_attn_fwd_flops(counts, w.H, w.D)
