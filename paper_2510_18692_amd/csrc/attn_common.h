@@ -1,7 +1,7 @@
 // Pieces shared by the forward and backward group-attention kernels.
 #pragma once
 
-#include "moga_common.h"
+#include "lds_pipe.h"
 
 namespace moga {
 
@@ -72,39 +72,10 @@ __device__ __forceinline__ int swap_bits_2_3(int x) {
   return (x & ~12) | ((x & 4) << 1) | ((x & 8) >> 1);
 }
 
-// Transposed LDS read: the 16 lanes of a block each point at 4 consecutive bf16; lane i gets,
-// for e = 0..3, element i%4 of the 4 bf16 that lane 4e + i/4 pointed at.
-__device__ __forceinline__ short4_t lds_read_tr16(const unsigned short* p) {
-  return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-      (short4_t __attribute__((address_space(3)))*)(p));
-}
-
 // XOR swizzle of the 16-byte chunk index inside an unpadded 256-byte LDS row (128 bf16):
 // chunk' = chunk ^ lds_swizzle(row).  The two low row bits land in chunk bits 3:2 and row bits
 // 3:2 in chunk bits 1:0, which spreads both the row-per-lane 16-byte reads and the 4-row
 // transposed reads over all banks.
 __device__ __forceinline__ int lds_swizzle(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
-
-// Direct global -> LDS load of 16 bytes per lane: the wave writes 1 KB starting at the
-// wave-uniform LDS byte address `lds_wave_base`, lane i at byte 16*i.  Issued through inline
-// assembly so that the compiler does not make later LDS reads of *other* buffers wait for it;
-// the caller waits (s_waitcnt vmcnt(0)) and synchronises before anyone reads the target.
-__device__ __forceinline__ void lds_dma16(const void* gptr, unsigned lds_wave_base) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-               :
-               : "s"(lds_wave_base), "v"(gptr)
-               : "memory");
-}
-
-// LDS byte address of a __shared__ object, made wave-uniform.
-__device__ __forceinline__ unsigned lds_addr_uniform(const void* p) {
-  return __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)p);
-}
-
-__device__ __forceinline__ bf16x8_t concat_tr(short4_t lo, short4_t hi) {
-  typedef short short8_t __attribute__((ext_vector_type(8)));
-  short8_t s = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-  return __builtin_bit_cast(bf16x8_t, s);
-}
 
 }  // namespace moga

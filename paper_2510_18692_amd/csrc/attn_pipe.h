@@ -16,38 +16,12 @@ constexpr int kPipeNBuf = 4;                      // LDS ring: tiles of 64 keys
 constexpr int kPipeAhead = 2;                     // tiles in flight beyond the one being waited for
 constexpr int kPipeTileBytes = 64 * kHeadDim * 2; // 16 KB per K (or V) tile
 
-// s_waitcnt immediates (gfx9 encoding): vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8.
-constexpr int waitcnt_vm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
-
-__device__ __forceinline__ const void* uniform_ptr(const void* p) {
-  const uint64_t v = (uint64_t)(uintptr_t)p;
-  // readfirstlane returns a signed int: go through unsigned so the low half is not sign-extended
-  const uint64_t lo = (unsigned)__builtin_amdgcn_readfirstlane((unsigned)v);
-  const uint64_t hi = (unsigned)__builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
-  return (const void*)(uintptr_t)(lo | (hi << 32));
-}
-
-__device__ __forceinline__ void lds_dma16_soff(const void* base, unsigned byte_off, unsigned lds_wave_base) {
-  lds_wave_base = __builtin_amdgcn_readfirstlane(lds_wave_base);
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-               :
-               : "s"(lds_wave_base), "v"(byte_off), "s"(base)
-               : "memory");
-}
-
 struct PipeLane {
   // per-lane LDS byte addresses inside buffer 0 (swizzle applied); other buffers, the second
   // 32-key half and the second 16-key MFMA step are compile-time offsets
   unsigned k_addr[8];      // K fragment for d chunk pair ks (row = permuted lane row)
   unsigned v_addr[4][2];   // transposed V read for d tile dt, rows +0 / +4
 };
-
-__device__ __forceinline__ bf16x8_t lds_read_b128(unsigned addr) {
-  return *(const bf16x8_t __attribute__((address_space(3)))*)(uintptr_t)addr;
-}
-__device__ __forceinline__ short4_t lds_read_tr16_addr(unsigned addr) {
-  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4_t __attribute__((address_space(3)))*)(uintptr_t)addr);
-}
 
 __device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
 

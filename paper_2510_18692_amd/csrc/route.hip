@@ -9,7 +9,11 @@
 //     rounds.  Groups are the MFMA rows and tokens the columns, so a lane ends up holding
 //     half of one token's logits: argmax / softmax need one exchange between wave halves.
 //   * route_generic_kernel: any dtype / shape; one wave per token, fp32 FMA.
-#include "moga_common.h"
+// Backward: dr = d_gate * gate * (onehot(group) - probs), dW = dr^T X on bf16 MFMA (dr split in two
+// bf16 limbs) for bf16 X, else with fp32 FMAs; optional dX = dr W.
+#include <algorithm>
+
+#include "lds_pipe.h"
 
 namespace moga {
 
@@ -328,6 +332,151 @@ __global__ __launch_bounds__(256) void route_bwd_dx_kernel(
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// dW on the matrix cores (bf16 X, M <= 32, d a multiple of 256).
+//
+// dW^T[c, j] = sum_t X[t, c] dr[t, j] is a contraction over tokens.  A pre-pass writes dr as two
+// bf16 limbs (hi + lo carries 16 mantissa bits) in the B-operand order of the 32x32x16 MFMA:
+// [token block of 8][group 0..31][8 tokens], zero beyond M and beyond N.  The main kernel runs
+// one wave per block: the wave owns 256 columns of X and a range of 16-token steps, streams
+// [16 tokens x 256 columns] tiles of X plus the two dr limb tiles into its own LDS ring with
+// direct-to-LDS loads (three stages in flight, no barriers: a wave only reads what it loaded),
+// reads X^T fragments with transposed LDS reads and accumulates eight 32x32 blocks of dW^T.
+// Partial sums go to partial[split][c][32] and a second kernel reduces over the splits.
+// ---------------------------------------------------------------------------------------
+constexpr int kDwCols = 256;                          // columns of X per wave
+constexpr int kDwTok = 16;                            // tokens per stage = one MFMA contraction step
+constexpr int kDwStages = 4;                          // ring slots
+constexpr int kDwXBytes = kDwTok * kDwCols * 2;       // 8 KB
+constexpr int kDwStageBytes = kDwXBytes + 2048;       // + dr hi, dr lo (1 KB each)
+constexpr int kDwDmaPerStage = kDwXBytes / 1024 + 2;  // direct-to-LDS instructions per stage
+
+__global__ __launch_bounds__(256) void route_bwd_dr_pack_kernel(
+    const float* __restrict__ probs, const int32_t* __restrict__ group,
+    const float* __restrict__ gate, const float* __restrict__ d_gate, int64_t N, int M,
+    int64_t blocks8, uintx4_t* __restrict__ dr_hi, uintx4_t* __restrict__ dr_lo) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t tb = idx >> 5;
+  const int j = (int)(idx & 31);
+  if (tb >= blocks8) return;
+  unsigned short hi[8], lo[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int64_t tok = tb * 8 + i;
+    float v = 0.f;
+    if (tok < N && j < M) {
+      const float coef = d_gate[tok] * gate[tok];
+      const float onehot = (group[tok] == j) ? 1.f : 0.f;
+      v = coef * (onehot - probs[tok * M + j]);
+    }
+    hi[i] = f32_to_bf16_bits(v);
+    lo[i] = f32_to_bf16_bits(v - bf16_bits_to_f32(hi[i]));
+  }
+  const uintx4_t ph = {hi[0] | ((unsigned)hi[1] << 16), hi[2] | ((unsigned)hi[3] << 16),
+                       hi[4] | ((unsigned)hi[5] << 16), hi[6] | ((unsigned)hi[7] << 16)};
+  const uintx4_t pl = {lo[0] | ((unsigned)lo[1] << 16), lo[2] | ((unsigned)lo[3] << 16),
+                       lo[4] | ((unsigned)lo[5] << 16), lo[6] | ((unsigned)lo[7] << 16)};
+  dr_hi[idx] = ph;
+  dr_lo[idx] = pl;
+}
+
+// Chunk swizzle of the X tile in LDS (rows of 512 B = 32 chunks of 16 B): chunk' = chunk ^ this.
+// The four rows a transposed read touches land in four different 64-byte bank groups.
+__device__ __forceinline__ int dw_swizzle(int row) { return (row & 3) << 2; }
+
+__global__ __launch_bounds__(64) void route_bwd_dw_mfma_kernel(
+    const unsigned short* __restrict__ x, const uintx4_t* __restrict__ dr_hi,
+    const uintx4_t* __restrict__ dr_lo, int64_t N, int d, int nslabs, int splits,
+    int64_t steps_per_split, int64_t total_steps, float* __restrict__ partial) {
+  __shared__ __attribute__((aligned(1024))) unsigned char ring[kDwStages * kDwStageBytes];
+  const int lane = threadIdx.x;
+  const int r = lane & 31, h = lane >> 5;
+  // Blocks are dealt round-robin to the 8 XCDs; consecutive blocks of one XCD take the column
+  // slabs of one token split, so its dr tiles are shared through that XCD's L2.
+  const int64_t k = blockIdx.x >> 3;
+  const int split = (int)(k / nslabs) * 8 + (int)(blockIdx.x & 7);
+  const int slab = (int)(k % nslabs);
+  if (split >= splits) return;
+  const int64_t s0 = (int64_t)split * steps_per_split;
+  const int64_t s1 = min(total_steps, s0 + steps_per_split);
+  const int nst = (int)(s1 - s0);
+
+  floatx16_t acc[8];
+#pragma unroll
+  for (int cb = 0; cb < 8; ++cb)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[cb][v] = 0.f;
+
+  const unsigned lds0 = lds_addr_uniform(&ring[0]);
+  // direct-to-LDS: instruction q of a stage covers token rows 2q, 2q+1 (32 chunks each)
+  const int dma_row = lane >> 5, dma_pos = lane & 31;
+  const unsigned short* xslab = x + (int64_t)slab * kDwCols;
+  auto issue = [&](int64_t step, int slot) {
+    if (step > total_steps - 1) step = total_steps - 1;   // beyond the range: valid memory, never read back
+    const int64_t tok0 = step * kDwTok;
+    const int last = (int)min((int64_t)(kDwTok - 1), N - 1 - tok0);
+    const void* xb = uniform_ptr(xslab + tok0 * (int64_t)d);
+    const unsigned base = lds0 + slot * kDwStageBytes;
+#pragma unroll
+    for (int q = 0; q < kDwTok / 2; ++q) {
+      const int row = 2 * q + dma_row;
+      const unsigned off = (unsigned)min(row, last) * (unsigned)(d * 2) + ((dma_pos ^ dw_swizzle(row)) << 4);
+      lds_dma16_soff(xb, off, base + q * 1024);
+    }
+    const int64_t tb = step * 2 * 32;   // two 8-token blocks of 32 groups, 16 bytes each
+    lds_dma16_soff(uniform_ptr(dr_hi + tb), (unsigned)lane * 16u, base + kDwXBytes);
+    lds_dma16_soff(uniform_ptr(dr_lo + tb), (unsigned)lane * 16u, base + kDwXBytes + 1024);
+  };
+
+  // transposed reads: lane gets X^T[column 32*cb + lane%32][tokens 8h .. 8h+7] from rows tr_r + {0..3}
+  // (and + 4), 16-byte chunk 4*cb + tr_c, element offset tr_e
+  const int tr_r = 8 * h + ((lane & 15) >> 2);
+  const int tr_c = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
+  const int tr_e = 4 * (lane & 1);
+  unsigned a_addr[8];
+#pragma unroll
+  for (int cb = 0; cb < 8; ++cb)
+    a_addr[cb] = (unsigned)(uintptr_t)&ring[0] + tr_r * 512 + (((4 * cb + tr_c) ^ dw_swizzle(tr_r)) << 4) + tr_e * 2;
+  const unsigned b_addr = (unsigned)(uintptr_t)&ring[0] + kDwXBytes + lane * 16;
+
+#pragma unroll
+  for (int t = 0; t < kDwStages - 1; ++t) issue(s0 + t, t);
+  for (int s = 0; s < nst; ++s) {
+    issue(s0 + s + kDwStages - 1, (s + kDwStages - 1) & (kDwStages - 1));
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kDwDmaPerStage * (kDwStages - 1)) : "memory");
+    const unsigned so = (unsigned)(s & (kDwStages - 1)) * kDwStageBytes;
+    const bf16x8_t bh = lds_read_b128(b_addr + so);
+    const bf16x8_t bl = lds_read_b128(b_addr + so + 1024);
+#pragma unroll
+    for (int cb = 0; cb < 8; ++cb) {
+      const bf16x8_t a = concat_tr(lds_read_tr16_addr(a_addr[cb] + so), lds_read_tr16_addr(a_addr[cb] + so + 4 * 512));
+      acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bh, acc[cb], 0, 0, 0);
+      acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bl, acc[cb], 0, 0, 0);
+    }
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // nothing may land in LDS after the block ends
+
+  // accumulator register v of lane (r, h): column 8*(v/4) + 4*h + v%4 of the block, group r
+  float* out = partial + ((int64_t)split * d + (int64_t)slab * kDwCols) * 32 + r;
+#pragma unroll
+  for (int cb = 0; cb < 8; ++cb)
+#pragma unroll
+    for (int v = 0; v < 16; ++v)
+      out[(int64_t)(32 * cb + 8 * (v >> 2) + 4 * h + (v & 3)) * 32] = acc[cb][v];
+}
+
+__global__ __launch_bounds__(256) void route_bwd_dw_reduce_t_kernel(
+    const float* __restrict__ partial /* [splits][d][32] */, int splits, int d, int M,
+    float* __restrict__ d_w) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t n = (int64_t)d * 32;
+  if (i >= n) return;
+  float s = 0.f;
+  for (int k = 0; k < splits; ++k) s += partial[(int64_t)k * n + i];
+  const int c = (int)(i >> 5), j = (int)(i & 31);
+  if (j < M) d_w[(int64_t)j * d + c] = s;
+}
+
 static int route_bwd_splits(int64_t N) {
   int64_t s = (N + 2047) / 2048;
   if (s < 1) s = 1;
@@ -335,12 +484,43 @@ static int route_bwd_splits(int64_t N) {
   return (int)s;
 }
 
+// Launch plan of the matrix-core dW path.
+struct DwPlan {
+  int nslabs, splits;
+  int64_t total_steps, steps_per_split;
+  size_t dr_bytes, partial_bytes;   // one dr limb array; the partial sums
+};
+
+static bool route_bwd_mfma_ok(int x_dtype, int M, int d) {
+  return x_dtype == MOGA_BF16 && M <= 32 && d % kDwCols == 0;
+}
+
+static DwPlan route_bwd_plan(int64_t N, int d) {
+  DwPlan p;
+  p.nslabs = d / kDwCols;
+  p.total_steps = (N + kDwTok - 1) / kDwTok;
+  int64_t splits = 2048 / p.nslabs;                       // about 8 waves per CU
+  splits = std::min<int64_t>(splits, (p.total_steps + 7) / 8);   // at least 128 tokens per split
+  splits = std::max<int64_t>(1, std::min<int64_t>(splits, 256));
+  p.steps_per_split = (p.total_steps + splits - 1) / splits;
+  p.splits = (int)((p.total_steps + p.steps_per_split - 1) / p.steps_per_split);   // no empty split
+  p.dr_bytes = (size_t)p.total_steps * 2 * 32 * 16;
+  p.partial_bytes = (size_t)p.splits * (size_t)d * 32 * sizeof(float);
+  return p;
+}
+
 }  // namespace moga
 
 using namespace moga;
 
 extern "C" size_t moga_route_bwd_ws_bytes(int64_t N, int M, int d_model) {
-  return (size_t)route_bwd_splits(N) * (size_t)M * (size_t)d_model * sizeof(float);
+  // the larger of the two paths, so the size does not depend on the dtype of X
+  size_t need = (size_t)route_bwd_splits(N) * (size_t)M * (size_t)d_model * sizeof(float);
+  if (N > 0 && route_bwd_mfma_ok(MOGA_BF16, M, d_model)) {
+    const DwPlan p = route_bwd_plan(N, d_model);
+    need = std::max(need, 2 * p.dr_bytes + p.partial_bytes);
+  }
+  return need;
 }
 
 extern "C" int moga_route(const void* x, int x_dtype, const float* w, const float* bias,
@@ -393,18 +573,35 @@ extern "C" int moga_route_bwd(const void* x, int x_dtype, const float* w, const 
   if (!x || !w || !probs || !group || !gate || !d_gate) return MOGA_ERR_INVALID_ARG;
   const size_t need = moga_route_bwd_ws_bytes(N, M, d_model);
   if (!ws || ws_bytes < need) return MOGA_ERR_WORKSPACE;
-  const int splits = route_bwd_splits(N);
-  int64_t tps = (N + splits - 1) / splits;
-  tps = (tps + kRbTok - 1) / kRbTok * kRbTok;
-  dim3 grid((d_model + 255) / 256, splits, (M + kRbMB - 1) / kRbMB);
-  float* partial = (float*)ws;
-  if (x_dtype == MOGA_F32)
-    route_bwd_dw_partial_kernel<float><<<grid, 256, 0, st>>>((const float*)x, probs, group, gate,
-                                                            d_gate, N, d_model, M, tps, partial);
-  else
-    route_bwd_dw_partial_kernel<unsigned short><<<grid, 256, 0, st>>>(
-        (const unsigned short*)x, probs, group, gate, d_gate, N, d_model, M, tps, partial);
-  route_bwd_dw_reduce_kernel<<<(unsigned)((md + 255) / 256), 256, 0, st>>>(partial, splits, md, d_w);
+  if (route_bwd_mfma_ok(x_dtype, M, d_model)) {
+    if (!aligned16(x) || !aligned16(ws)) return MOGA_ERR_INVALID_ARG;
+    const DwPlan p = route_bwd_plan(N, d_model);
+    uintx4_t* dr_hi = (uintx4_t*)ws;
+    uintx4_t* dr_lo = (uintx4_t*)((char*)ws + p.dr_bytes);
+    float* partial = (float*)((char*)ws + 2 * p.dr_bytes);
+    const int64_t blocks8 = p.total_steps * 2;
+    route_bwd_dr_pack_kernel<<<(unsigned)((blocks8 * 32 + 255) / 256), 256, 0, st>>>(
+        probs, group, gate, d_gate, N, M, blocks8, dr_hi, dr_lo);
+    const unsigned blocks = (unsigned)((p.splits + 7) / 8 * 8 * p.nslabs);
+    route_bwd_dw_mfma_kernel<<<blocks, 64, 0, st>>>((const unsigned short*)x, dr_hi, dr_lo, N, d_model,
+                                                    p.nslabs, p.splits, p.steps_per_split,
+                                                    p.total_steps, partial);
+    route_bwd_dw_reduce_t_kernel<<<(unsigned)(((int64_t)d_model * 32 + 255) / 256), 256, 0, st>>>(
+        partial, p.splits, d_model, M, d_w);
+  } else {
+    const int splits = route_bwd_splits(N);
+    int64_t tps = (N + splits - 1) / splits;
+    tps = (tps + kRbTok - 1) / kRbTok * kRbTok;
+    dim3 grid((d_model + 255) / 256, splits, (M + kRbMB - 1) / kRbMB);
+    float* partial = (float*)ws;
+    if (x_dtype == MOGA_F32)
+      route_bwd_dw_partial_kernel<float><<<grid, 256, 0, st>>>((const float*)x, probs, group, gate,
+                                                              d_gate, N, d_model, M, tps, partial);
+    else
+      route_bwd_dw_partial_kernel<unsigned short><<<grid, 256, 0, st>>>(
+          (const unsigned short*)x, probs, group, gate, d_gate, N, d_model, M, tps, partial);
+    route_bwd_dw_reduce_kernel<<<(unsigned)((md + 255) / 256), 256, 0, st>>>(partial, splits, md, d_w);
+  }
   if (d_x) {
     dim3 gx((unsigned)((N + kRbTok - 1) / kRbTok), (d_model + 255) / 256);
     route_bwd_dx_kernel<<<gx, 256, 0, st>>>(w, probs, group, gate, d_gate, N, d_model, M, d_x);
