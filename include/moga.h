@@ -50,7 +50,8 @@ typedef enum {
   MOGA_OP_PERMUTE = 1,
   MOGA_OP_ATTN_FWD = 2,
   MOGA_OP_ATTN_BWD = 3,
-  MOGA_OP_ROUTE_BWD = 4
+  MOGA_OP_ROUTE_BWD = 4,
+  MOGA_OP_BALANCE_LOSS = 5
 } moga_op;
 
 /* Human-readable name of a status code (static storage, never NULL). */
@@ -153,6 +154,30 @@ int moga_route_bwd(const void* x, int x_dtype, const float* w, const float* prob
                    const int32_t* group, const float* gate, const float* d_gate,
                    int64_t N, int d_model, int M, float* d_w, float* d_x_or_null,
                    void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Group balancing loss, Eqs. 6-8 (Section 3.2; alpha = 0.1 in the paper's training setup):
+ *   frac[i] = (1/N) #{x : group[x] = i}                   (Eq. 7)
+ *   prob[i] = (1/N) sum_{x : group[x] = i} gate[x]        (Eq. 8: the sum runs over the tokens
+ *                                                          assigned to i, gate = p(g(x)|x))
+ *   loss    = alpha * M * sum_i frac[i] * prob[i]         (Eq. 6)
+ * group [N] int32 and gate [N] fp32 as written by moga_route.  Outputs (device, fp32): loss [1],
+ * frac [M], prob [M], all required.  Sums are order-independent (integer accumulation), so the
+ * result is bit-reproducible.  Tokens whose group lies outside [0, M) are ignored.
+ */
+int moga_balance_loss(const int32_t* group, const float* gate, int64_t N, int M, float alpha,
+                      float* loss, float* frac, float* prob, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Gradient of the balancing loss with respect to the gate (frac is piecewise constant in the
+ * router weights, so only prob carries a gradient):
+ *   d_gate[x] (+)= d_loss * alpha * M * frac[group[x]] / N
+ * frac [M] from moga_balance_loss; d_loss is the upstream scalar gradient (host value).  With
+ * accumulate != 0 the term is added to d_gate (e.g. the output of moga_unpermute_bwd, before
+ * moga_route_bwd); otherwise d_gate is overwritten.
+ */
+int moga_balance_loss_bwd(const int32_t* group, const float* frac, int64_t N, int M, float alpha,
+                          float d_loss, int accumulate, float* d_gate, void* stream);
 
 #ifdef __cplusplus
 }

@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmoga.so")
 
 MOGA_F32, MOGA_BF16 = 0, 1
-OP_ROUTE, OP_PERMUTE, OP_ATTN_FWD, OP_ATTN_BWD, OP_ROUTE_BWD = range(5)
+OP_ROUTE, OP_PERMUTE, OP_ATTN_FWD, OP_ATTN_BWD, OP_ROUTE_BWD, OP_BALANCE_LOSS = range(6)
 
 _c = ctypes
 _vp, _i64, _i32, _f32, _sz = _c.c_void_p, _c.c_int64, _c.c_int, _c.c_float, _c.c_size_t
@@ -37,6 +37,8 @@ _SIGNATURES = {
     "moga_permute_bwd": (_i32, [_vp, _vp, _vp, _i32, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp]),
     "moga_route_bwd": (_i32, [_vp, _i32, _vp, _vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _vp, _vp,
                               _sz, _vp]),
+    "moga_balance_loss": (_i32, [_vp, _vp, _i64, _i32, _f32, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "moga_balance_loss_bwd": (_i32, [_vp, _vp, _i64, _i32, _f32, _f32, _i32, _vp, _vp]),
 }
 EXPORTS = tuple(_SIGNATURES)
 
@@ -214,6 +216,32 @@ def moga_route_bwd(x, w, probs, group, gate, d_gate, want_dx=False, stream=None)
                                _p(d_w), _p(d_x), _p(ws), ws.numel(), _stream(stream))
     _check("moga_route_bwd", st)
     return d_w, d_x
+
+
+def moga_balance_loss(group, gate, M, alpha, stream=None):
+    """Eqs. 6-8 -> (loss f32 [1], frac f32 [M], prob f32 [M]), all on the device."""
+    N = group.shape[0]
+    dev = group.device
+    loss = torch.empty(1, dtype=torch.float32, device=dev)
+    frac = torch.empty(M, dtype=torch.float32, device=dev)
+    prob = torch.empty(M, dtype=torch.float32, device=dev)
+    ws = _ws(workspace_bytes(OP_BALANCE_LOSS, N, 0, 0, M, 0, MOGA_F32), dev)
+    st = load().moga_balance_loss(_p(group), _p(gate), N, M, float(alpha), _p(loss), _p(frac), _p(prob),
+                                  _p(ws), ws.numel(), _stream(stream))
+    _check("moga_balance_loss", st)
+    return loss, frac, prob
+
+
+def moga_balance_loss_bwd(group, frac, alpha, d_loss=1.0, d_gate=None, stream=None):
+    """Adds d_loss * dL/d gate to `d_gate` (in place) or returns a new tensor when d_gate is None."""
+    N, M = group.shape[0], frac.shape[0]
+    accumulate = d_gate is not None
+    if d_gate is None:
+        d_gate = torch.empty(N, dtype=torch.float32, device=group.device)
+    st = load().moga_balance_loss_bwd(_p(group), _p(frac), N, M, float(alpha), float(d_loss),
+                                      int(accumulate), _p(d_gate), _stream(stream))
+    _check("moga_balance_loss_bwd", st)
+    return d_gate
 
 
 def moga_forward(x, w, q, k, v, softmax_scale, want_probs=True, stream=None):

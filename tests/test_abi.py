@@ -21,6 +21,7 @@ def test_header_declares_the_expected_entry_points():
     names = declared_functions()
     for n in ("moga_route", "moga_permute", "moga_group_attn_fwd", "moga_group_attn_bwd",
               "moga_unpermute", "moga_unpermute_bwd", "moga_permute_bwd", "moga_route_bwd",
+              "moga_balance_loss", "moga_balance_loss_bwd",
               "moga_workspace_bytes", "moga_status_string", "moga_version"):
         assert n in names
 
@@ -87,3 +88,10 @@ def test_invalid_arguments_return_status_codes_without_a_gpu():
                             None, None, None, None, 0, None) == -3
     assert lib.moga_route_bwd(fake, 1, fake, fake, fake, fake, fake, 4096, 128, 8, fake, None, fake, 16,
                               None) == -3
+    # balancing loss: missing outputs, too many groups, short workspace
+    assert lib.moga_balance_loss(fake, fake, 64, 8, 0.1, None, fake, fake, fake, 4096, None) == -1
+    assert lib.moga_balance_loss(fake, fake, 64, 257, 0.1, fake, fake, fake, fake, 8192, None) == -2
+    assert lib.moga_balance_loss(fake, fake, 64, 8, 0.1, fake, fake, fake, fake, 8, None) == -3
+    assert lib.moga_balance_loss_bwd(fake, None, 64, 8, 0.1, 1.0, 0, fake, None) == -1
+    assert lib.moga_balance_loss_bwd(fake, fake, 0, 8, 0.1, 1.0, 0, fake, None) == 0
+    assert binding.workspace_bytes(binding.OP_BALANCE_LOSS, 4096, 0, 0, 32, 0, 0) >= 32 * 12

@@ -170,6 +170,22 @@ def test_router_weight_gradient_in_full_with_seeded_upstream(name):
     assert rl <= 5e-3
 
 
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("name", NAMES)
+def test_balancing_loss_over_all_tokens(name):
+    c = run(name)
+    w, rt = c["w"], c["rt"]
+    L, F, Pm = orc.balance_loss(rt["group"], rt["gate"], w.M, 0.1)
+    group_t, gate_t = torch.from_numpy(rt["group"]).cuda(), torch.from_numpy(rt["gate"]).cuda()
+    loss, frac, prob = mg.moga_balance_loss(group_t, gate_t, w.M, 0.1)
+    say(f"  balancing loss {float(loss.item()):.7f} (oracle {L:.7f}), L/alpha = {L / 0.1:.4f}")
+    np.testing.assert_allclose(float(loss.item()), L, rtol=1e-6)
+    np.testing.assert_allclose(P.to64(frac), F, rtol=1e-6)
+    np.testing.assert_allclose(P.to64(prob), Pm, rtol=1e-6)
+    dg = mg.moga_balance_loss_bwd(group_t, frac, 0.1)
+    np.testing.assert_allclose(P.to64(dg), orc.balance_loss_bwd(rt["group"], w.M, 0.1), rtol=2e-6)
+
+
 def test_release_cached_run():
     _cache.clear()
     torch.cuda.empty_cache()
