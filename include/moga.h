@@ -33,7 +33,8 @@
 extern "C" {
 #endif
 
-#define MOGA_MAX_GROUPS 256
+#define MOGA_MAX_GROUPS 256          /* router groups M */
+#define MOGA_MAX_SEGMENTS (1 << 24)  /* static groups G of the moga_varlen_* calls */
 
 typedef enum {
   MOGA_OK = 0,
@@ -51,7 +52,9 @@ typedef enum {
   MOGA_OP_ATTN_FWD = 2,
   MOGA_OP_ATTN_BWD = 3,
   MOGA_OP_ROUTE_BWD = 4,
-  MOGA_OP_BALANCE_LOSS = 5
+  MOGA_OP_BALANCE_LOSS = 5,
+  MOGA_OP_VARLEN_ATTN_FWD = 6, /* N = Nq, M = G */
+  MOGA_OP_VARLEN_ATTN_BWD = 7  /* N = Nq, M = G */
 } moga_op;
 
 /* Human-readable name of a status code (static storage, never NULL). */
@@ -154,6 +157,37 @@ int moga_route_bwd(const void* x, int x_dtype, const float* w, const float* prob
                    const int32_t* group, const float* gate, const float* d_gate,
                    int64_t N, int d_model, int M, float* d_w, float* d_x_or_null,
                    void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Attention inside static groups whose queries and keys are listed separately (Section 3.2,
+ * "Spatial-Temporal Group Attention": a group's keys and values may hold more rows than its
+ * queries, e.g. latent frames added from adjacent shots).  Group g attends the query rows
+ * cu_seqlens_q[g] .. cu_seqlens_q[g+1] of qh [H, Nq, D] to the key/value rows
+ * cu_seqlens_k[g] .. cu_seqlens_k[g+1] of kh, vh [H, Nk, D]; Eq. 1 per group and head, as in
+ * moga_group_attn_fwd (which is the case cu_seqlens_k == cu_seqlens_q, Nk == Nq).
+ * cu_seqlens_q, cu_seqlens_k: [G + 1] int32 on the device, non-decreasing, first entry 0, last
+ * entry Nq / Nk.  G in [1, MOGA_MAX_SEGMENTS].  Queries of a group without keys get oh = 0 and
+ * lse = -inf.  Outputs oh [H, Nq, D], lse [H, Nq] fp32.  Workspace: MOGA_OP_VARLEN_ATTN_FWD.
+ */
+int moga_varlen_attn_fwd(const void* qh, const void* kh, const void* vh, int dtype,
+                         int64_t Nq, int64_t Nk, int H, int D,
+                         const int32_t* cu_seqlens_q, const int32_t* cu_seqlens_k, int G,
+                         float softmax_scale, void* oh, float* lse,
+                         void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Backward of moga_varlen_attn_fwd (same formulas as moga_group_attn_bwd, per group and head).
+ * d_oh, oh, d_qh [H, Nq, D]; d_kh, d_vh [H, Nk, D]: one gradient row per listed key row (a token
+ * listed as a key by several groups has several rows; moga_gather_rows_bwd adds them up).
+ * Keys of a group without queries, and queries of a group without keys, get zero gradients.
+ * Workspace: MOGA_OP_VARLEN_ATTN_BWD.
+ */
+int moga_varlen_attn_bwd(const void* d_oh, const void* qh, const void* kh, const void* vh,
+                         const void* oh, const float* lse, int dtype,
+                         int64_t Nq, int64_t Nk, int H, int D,
+                         const int32_t* cu_seqlens_q, const int32_t* cu_seqlens_k, int G,
+                         float softmax_scale, void* d_qh, void* d_kh, void* d_vh,
+                         void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Group balancing loss, Eqs. 6-8 (Section 3.2; alpha = 0.1 in the paper's training setup):

@@ -17,7 +17,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmoga.so")
 
 MOGA_F32, MOGA_BF16 = 0, 1
-OP_ROUTE, OP_PERMUTE, OP_ATTN_FWD, OP_ATTN_BWD, OP_ROUTE_BWD, OP_BALANCE_LOSS = range(6)
+(OP_ROUTE, OP_PERMUTE, OP_ATTN_FWD, OP_ATTN_BWD, OP_ROUTE_BWD, OP_BALANCE_LOSS, OP_VARLEN_ATTN_FWD,
+ OP_VARLEN_ATTN_BWD) = range(8)
 
 _c = ctypes
 _vp, _i64, _i32, _f32, _sz = _c.c_void_p, _c.c_int64, _c.c_int, _c.c_float, _c.c_size_t
@@ -37,6 +38,10 @@ _SIGNATURES = {
     "moga_permute_bwd": (_i32, [_vp, _vp, _vp, _i32, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp]),
     "moga_route_bwd": (_i32, [_vp, _i32, _vp, _vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _vp, _vp,
                               _sz, _vp]),
+    "moga_varlen_attn_fwd": (_i32, [_vp, _vp, _vp, _i32, _i64, _i64, _i32, _i32, _vp, _vp, _i32, _f32, _vp, _vp,
+                                    _vp, _sz, _vp]),
+    "moga_varlen_attn_bwd": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _i64, _i64, _i32, _i32, _vp, _vp, _i32,
+                                    _f32, _vp, _vp, _vp, _vp, _sz, _vp]),
     "moga_balance_loss": (_i32, [_vp, _vp, _i64, _i32, _f32, _vp, _vp, _vp, _vp, _sz, _vp]),
     "moga_balance_loss_bwd": (_i32, [_vp, _vp, _i64, _i32, _f32, _f32, _i32, _vp, _vp]),
 }
@@ -216,6 +221,35 @@ def moga_route_bwd(x, w, probs, group, gate, d_gate, want_dx=False, stream=None)
                                _p(d_w), _p(d_x), _p(ws), ws.numel(), _stream(stream))
     _check("moga_route_bwd", st)
     return d_w, d_x
+
+
+def moga_varlen_attn_fwd(qh, kh, vh, cu_seqlens_q, cu_seqlens_k, softmax_scale, stream=None):
+    """qh [H, Nq, D]; kh, vh [H, Nk, D] -> (oh [H, Nq, D], lse f32 [H, Nq])"""
+    H, Nq, D = qh.shape
+    Nk = kh.shape[1]
+    G = cu_seqlens_q.shape[0] - 1
+    oh = torch.empty_like(qh)
+    lse = torch.empty((H, Nq), dtype=torch.float32, device=qh.device)
+    ws = _ws(workspace_bytes(OP_VARLEN_ATTN_FWD, Nq, H, D, G, 0, _dt(qh)), qh.device)
+    st = load().moga_varlen_attn_fwd(_p(qh), _p(kh), _p(vh), _dt(qh), Nq, Nk, H, D, _p(cu_seqlens_q),
+                                     _p(cu_seqlens_k), G, float(softmax_scale), _p(oh), _p(lse), _p(ws),
+                                     ws.numel(), _stream(stream))
+    _check("moga_varlen_attn_fwd", st)
+    return oh, lse
+
+
+def moga_varlen_attn_bwd(d_oh, qh, kh, vh, oh, lse, cu_seqlens_q, cu_seqlens_k, softmax_scale, stream=None):
+    """-> (d_qh [H, Nq, D], d_kh, d_vh [H, Nk, D])"""
+    H, Nq, D = qh.shape
+    Nk = kh.shape[1]
+    G = cu_seqlens_q.shape[0] - 1
+    d_qh, d_kh, d_vh = torch.empty_like(qh), torch.empty_like(kh), torch.empty_like(vh)
+    ws = _ws(workspace_bytes(OP_VARLEN_ATTN_BWD, Nq, H, D, G, 0, _dt(qh)), qh.device)
+    st = load().moga_varlen_attn_bwd(_p(d_oh), _p(qh), _p(kh), _p(vh), _p(oh), _p(lse), _dt(qh), Nq, Nk, H, D,
+                                     _p(cu_seqlens_q), _p(cu_seqlens_k), G, float(softmax_scale), _p(d_qh),
+                                     _p(d_kh), _p(d_vh), _p(ws), ws.numel(), _stream(stream))
+    _check("moga_varlen_attn_bwd", st)
+    return d_qh, d_kh, d_vh
 
 
 def moga_balance_loss(group, gate, M, alpha, stream=None):

@@ -5,6 +5,8 @@ extern "C" size_t moga_permute_ws_bytes(int64_t N, int M);
 extern "C" size_t moga_route_bwd_ws_bytes(int64_t N, int M, int d_model);
 extern "C" size_t moga_attn_bwd_ws_bytes(int64_t N, int H, int D, int dtype);
 extern "C" size_t moga_balance_ws_bytes(int M);
+extern "C" size_t moga_varlen_attn_fwd_ws_bytes(int G);
+extern "C" size_t moga_varlen_attn_bwd_ws_bytes(int64_t Nq, int H, int G);
 
 extern "C" const char* moga_status_string(int status) {
   switch (status) {
@@ -17,7 +19,7 @@ extern "C" const char* moga_status_string(int status) {
   }
 }
 
-extern "C" int moga_version(void) { return 101; }
+extern "C" int moga_version(void) { return 102; }
 
 extern "C" size_t moga_workspace_bytes(int op, int64_t N, int H, int D, int M, int d_model,
                                        int dtype) {
@@ -27,6 +29,8 @@ extern "C" size_t moga_workspace_bytes(int op, int64_t N, int H, int D, int M, i
     case MOGA_OP_ATTN_BWD: return moga_attn_bwd_ws_bytes(N, H, D, dtype);
     case MOGA_OP_ROUTE_BWD: return moga_route_bwd_ws_bytes(N, M, d_model);
     case MOGA_OP_BALANCE_LOSS: return moga_balance_ws_bytes(M);
+    case MOGA_OP_VARLEN_ATTN_FWD: return moga_varlen_attn_fwd_ws_bytes(M);
+    case MOGA_OP_VARLEN_ATTN_BWD: return moga_varlen_attn_bwd_ws_bytes(N, H, M);
     default: return 0;
   }
 }

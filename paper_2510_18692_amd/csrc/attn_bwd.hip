@@ -63,8 +63,9 @@ template <int D>
 __global__ __launch_bounds__(64) void attn_bwd_dq_f32_kernel(
     const float* __restrict__ d_oh, const float* __restrict__ qh, const float* __restrict__ kh,
     const float* __restrict__ vh, const float* __restrict__ lse, const float* __restrict__ delta,
-    const int32_t* __restrict__ cu_seqlens, int M, int64_t N, int H, float scale, int tiles_per_head,
-    float* __restrict__ d_qh) {
+    const int32_t* __restrict__ cu_q, const int32_t* __restrict__ cu_k,
+    const int32_t* __restrict__ tile_start, int M, int64_t Nq, int64_t Nk, int H, float scale,
+    int tiles_per_head, float* __restrict__ d_qh) {
   __shared__ __attribute__((aligned(16))) float Ks[kF32BN][D];
   __shared__ __attribute__((aligned(16))) float Vs[kF32BN][D];
   __shared__ int s_start[MOGA_MAX_GROUPS + 1];
@@ -72,9 +73,15 @@ __global__ __launch_bounds__(64) void attn_bwd_dq_f32_kernel(
   const int head = blockIdx.x / tiles_per_head;
   const int tile = blockIdx.x - head * tiles_per_head;
   TileInfo ti;
-  if (!find_tile(cu_seqlens, M, kF32BM, tile, s_start, &s_found, ti)) return;
+  if (tile_start) {
+    if (!find_tile_presummed(tile_start, cu_q, M, kF32BM, tile, ti)) return;
+  } else if (!find_tile(cu_q, M, kF32BM, tile, s_start, &s_found, ti)) {
+    return;
+  }
   const int ge = ti.row_end;
-  const int64_t head_off = (int64_t)head * N;
+  const int kbeg = cu_k[ti.group], kend = cu_k[ti.group + 1];   // key rows of the group
+  const int64_t head_off = (int64_t)head * Nq;
+  const int64_t head_off_k = (int64_t)head * Nk;
   const int row = ti.tile_row + threadIdx.x;
   const bool valid = row < ge;
   const int64_t rr = head_off + (valid ? row : ge - 1);
@@ -83,20 +90,20 @@ __global__ __launch_bounds__(64) void attn_bwd_dq_f32_kernel(
   for (int cI = 0; cI < D; ++cI) { q[cI] = qh[rr * D + cI]; dO[cI] = d_oh[rr * D + cI]; dq[cI] = 0.f; }
   const float l = lse[rr], dl = delta[rr];
 
-  for (int kv0 = ti.row_begin; kv0 < ge; kv0 += kF32BN) {
+  for (int kv0 = kbeg; kv0 < kend; kv0 += kF32BN) {
     __syncthreads();
     for (int idx = threadIdx.x; idx < kF32BN * (D / 4); idx += 64) {
       const int r2 = idx / (D / 4), c4 = (idx - r2 * (D / 4)) * 4;
       floatx4_t kk = {0.f, 0.f, 0.f, 0.f}, vv = {0.f, 0.f, 0.f, 0.f};
-      if (kv0 + r2 < ge) {
-        kk = *(const floatx4_t*)(kh + (head_off + kv0 + r2) * D + c4);
-        vv = *(const floatx4_t*)(vh + (head_off + kv0 + r2) * D + c4);
+      if (kv0 + r2 < kend) {
+        kk = *(const floatx4_t*)(kh + (head_off_k + kv0 + r2) * D + c4);
+        vv = *(const floatx4_t*)(vh + (head_off_k + kv0 + r2) * D + c4);
       }
       *(floatx4_t*)&Ks[r2][c4] = kk;
       *(floatx4_t*)&Vs[r2][c4] = vv;
     }
     __syncthreads();
-    const int nk = min(kF32BN, ge - kv0);
+    const int nk = min(kF32BN, kend - kv0);
     for (int j = 0; j < nk; ++j) {
       float s = 0.f, dp = 0.f;
 #pragma unroll
@@ -117,8 +124,9 @@ template <int D>
 __global__ __launch_bounds__(64) void attn_bwd_dkdv_f32_kernel(
     const float* __restrict__ d_oh, const float* __restrict__ qh, const float* __restrict__ kh,
     const float* __restrict__ vh, const float* __restrict__ lse, const float* __restrict__ delta,
-    const int32_t* __restrict__ cu_seqlens, int M, int64_t N, int H, float scale, int tiles_per_head,
-    float* __restrict__ d_kh, float* __restrict__ d_vh) {
+    const int32_t* __restrict__ cu_q, const int32_t* __restrict__ cu_k,
+    const int32_t* __restrict__ tile_start, int M, int64_t Nq, int64_t Nk, int H, float scale,
+    int tiles_per_head, float* __restrict__ d_kh, float* __restrict__ d_vh) {
   __shared__ __attribute__((aligned(16))) float Qs[kF32BN][D];
   __shared__ __attribute__((aligned(16))) float dOs[kF32BN][D];
   __shared__ float s_lse[kF32BN], s_delta[kF32BN];
@@ -126,10 +134,16 @@ __global__ __launch_bounds__(64) void attn_bwd_dkdv_f32_kernel(
   __shared__ int s_found;
   const int head = blockIdx.x / tiles_per_head;
   const int tile = blockIdx.x - head * tiles_per_head;
-  TileInfo ti;
-  if (!find_tile(cu_seqlens, M, kF32BM, tile, s_start, &s_found, ti)) return;
+  TileInfo ti;   // tiles run over the key rows of the groups
+  if (tile_start) {
+    if (!find_tile_presummed(tile_start, cu_k, M, kF32BM, tile, ti)) return;
+  } else if (!find_tile(cu_k, M, kF32BM, tile, s_start, &s_found, ti)) {
+    return;
+  }
   const int ge = ti.row_end;
-  const int64_t head_off = (int64_t)head * N;
+  const int qbeg = cu_q[ti.group], qend = cu_q[ti.group + 1];   // query rows of the group
+  const int64_t head_off = (int64_t)head * Nk;     // key-side tensors
+  const int64_t head_off_q = (int64_t)head * Nq;   // query-side tensors
   const int row = ti.tile_row + threadIdx.x;
   const bool valid = row < ge;
   const int64_t rr = head_off + (valid ? row : ge - 1);
@@ -137,25 +151,25 @@ __global__ __launch_bounds__(64) void attn_bwd_dkdv_f32_kernel(
 #pragma unroll
   for (int cI = 0; cI < D; ++cI) { k[cI] = kh[rr * D + cI]; v[cI] = vh[rr * D + cI]; dk[cI] = 0.f; dv[cI] = 0.f; }
 
-  for (int q0 = ti.row_begin; q0 < ge; q0 += kF32BN) {
+  for (int q0 = qbeg; q0 < qend; q0 += kF32BN) {
     __syncthreads();
     for (int idx = threadIdx.x; idx < kF32BN * (D / 4); idx += 64) {
       const int r2 = idx / (D / 4), c4 = (idx - r2 * (D / 4)) * 4;
       floatx4_t qq = {0.f, 0.f, 0.f, 0.f}, dd = {0.f, 0.f, 0.f, 0.f};
-      if (q0 + r2 < ge) {
-        qq = *(const floatx4_t*)(qh + (head_off + q0 + r2) * D + c4);
-        dd = *(const floatx4_t*)(d_oh + (head_off + q0 + r2) * D + c4);
+      if (q0 + r2 < qend) {
+        qq = *(const floatx4_t*)(qh + (head_off_q + q0 + r2) * D + c4);
+        dd = *(const floatx4_t*)(d_oh + (head_off_q + q0 + r2) * D + c4);
       }
       *(floatx4_t*)&Qs[r2][c4] = qq;
       *(floatx4_t*)&dOs[r2][c4] = dd;
     }
     if (threadIdx.x < kF32BN) {
       const int g = q0 + threadIdx.x;
-      s_lse[threadIdx.x] = g < ge ? lse[head_off + g] : INFINITY;
-      s_delta[threadIdx.x] = g < ge ? delta[head_off + g] : 0.f;
+      s_lse[threadIdx.x] = g < qend ? lse[head_off_q + g] : INFINITY;
+      s_delta[threadIdx.x] = g < qend ? delta[head_off_q + g] : 0.f;
     }
     __syncthreads();
-    const int nq = min(kF32BN, ge - q0);
+    const int nq = min(kF32BN, qend - q0);
     for (int i = 0; i < nq; ++i) {
       float s = 0.f, dp = 0.f;
 #pragma unroll
@@ -182,17 +196,79 @@ extern "C" size_t moga_attn_bwd_ws_bytes(int64_t N, int H, int D, int dtype) {
   return 2 * (size_t)N * (size_t)H * sizeof(float);   // delta, lse * log2(e)
 }
 
+// Shared launcher.  ts_q / ts_k: NULL (tile lookup inside the kernels, M <= MOGA_MAX_GROUPS) or
+// space for the pre-summed first-tile indices over query rows / key rows (M + 1 ints each).
+static int launch_attn_bwd(const void* d_oh, const void* qh, const void* kh, const void* vh,
+                           const void* oh, const float* lse, int dtype, int64_t Nq, int64_t Nk, int H,
+                           const int32_t* cu_q, const int32_t* cu_k, int32_t* ts_q, int32_t* ts_k,
+                           int M, float softmax_scale, void* d_qh, void* d_kh, void* d_vh,
+                           float* delta, hipStream_t st) {
+  const int64_t rows = Nq * (int64_t)H;
+  if (dtype == MOGA_BF16) {
+    float* lse2 = delta + rows;   // holds -lse/scale; `delta` holds -delta
+    attn_bwd_delta_kernel<16, true><<<(unsigned)((rows * 16 + 255) / 256), 256, 0, st>>>(
+        (const uintx4_t*)d_oh, (const uintx4_t*)oh, lse, rows, 1.f / softmax_scale, delta, lse2);
+    if (Nk > 0) {
+      const int64_t tiles = max_tiles(Nk, M, 128);
+      const int64_t blocks = (tiles * H + 7) / 8 * 8;
+      if (blocks >= ((int64_t)1 << 31)) return MOGA_ERR_UNSUPPORTED;
+      if (ts_k) tile_start_kernel<<<1, 1024, 0, st>>>(cu_k, M, 128, ts_k);
+      attn_bwd_dkdv_pipe_kernel<4><<<(unsigned)blocks, 256, 0, st>>>(
+          (const unsigned short*)d_oh, (const unsigned short*)qh, (const unsigned short*)kh,
+          (const unsigned short*)vh, lse2, delta, cu_q, cu_k, ts_k, M, Nq, Nk, H, softmax_scale,
+          (int)tiles, (unsigned short*)d_kh, (unsigned short*)d_vh);
+    }
+    {
+      const int64_t tiles = max_tiles(Nq, M, 256);
+      const int64_t blocks = (tiles * H + 7) / 8 * 8;
+      if (blocks >= ((int64_t)1 << 31)) return MOGA_ERR_UNSUPPORTED;
+      if (ts_q) tile_start_kernel<<<1, 1024, 0, st>>>(cu_q, M, 256, ts_q);
+      attn_bwd_dq_pipe_kernel<8, 1><<<(unsigned)blocks, 512, 0, st>>>(
+          (const unsigned short*)d_oh, (const unsigned short*)qh, (const unsigned short*)kh,
+          (const unsigned short*)vh, lse2, delta, cu_q, cu_k, ts_q, M, Nq, Nk, H, softmax_scale,
+          (int)tiles, (unsigned short*)d_qh);
+    }
+  } else {
+    attn_bwd_delta_kernel<16, false><<<(unsigned)((rows * 16 + 255) / 256), 256, 0, st>>>(
+        (const uintx4_t*)d_oh, (const uintx4_t*)oh, lse, rows, 1.f, delta, nullptr);
+    if (Nk > 0) {
+      const int64_t tiles = max_tiles(Nk, M, kF32BM);
+      const int64_t blocks = tiles * H;
+      if (blocks >= ((int64_t)1 << 31)) return MOGA_ERR_UNSUPPORTED;
+      if (ts_k) tile_start_kernel<<<1, 1024, 0, st>>>(cu_k, M, kF32BM, ts_k);
+      attn_bwd_dkdv_f32_kernel<64><<<(unsigned)blocks, 64, 0, st>>>(
+          (const float*)d_oh, (const float*)qh, (const float*)kh, (const float*)vh, lse, delta,
+          cu_q, cu_k, ts_k, M, Nq, Nk, H, softmax_scale, (int)tiles, (float*)d_kh, (float*)d_vh);
+    }
+    const int64_t tiles = max_tiles(Nq, M, kF32BM);
+    const int64_t blocks = tiles * H;
+    if (blocks >= ((int64_t)1 << 31)) return MOGA_ERR_UNSUPPORTED;
+    if (ts_q) tile_start_kernel<<<1, 1024, 0, st>>>(cu_q, M, kF32BM, ts_q);
+    attn_bwd_dq_f32_kernel<64><<<(unsigned)blocks, 64, 0, st>>>(
+        (const float*)d_oh, (const float*)qh, (const float*)kh, (const float*)vh, lse, delta,
+        cu_q, cu_k, ts_q, M, Nq, Nk, H, softmax_scale, (int)tiles, (float*)d_qh);
+  }
+  return launch_status();
+}
+
+static int check_attn_bwd_args(int64_t Nq, int64_t Nk, int H, int D, int M, float softmax_scale, int dtype) {
+  if (Nq < 0 || Nk < 0 || H < 1 || D < 1 || M < 1) return MOGA_ERR_INVALID_ARG;
+  if (!(softmax_scale > 0.f) || !(softmax_scale < INFINITY)) return MOGA_ERR_INVALID_ARG;
+  if (dtype != MOGA_F32 && dtype != MOGA_BF16) return MOGA_ERR_UNSUPPORTED;
+  if (Nq >= ((int64_t)1 << 31) || Nk >= ((int64_t)1 << 31)) return MOGA_ERR_UNSUPPORTED;
+  if (dtype == MOGA_BF16 && D != 128) return MOGA_ERR_UNSUPPORTED;
+  if (dtype == MOGA_F32 && D != 64) return MOGA_ERR_UNSUPPORTED;
+  return MOGA_OK;
+}
+
 extern "C" int moga_group_attn_bwd(const void* d_oh, const void* qh, const void* kh, const void* vh,
                                    const void* oh, const float* lse, int dtype, int64_t N, int H,
                                    int D, const int32_t* cu_seqlens, int M, float softmax_scale,
                                    void* d_qh, void* d_kh, void* d_vh, void* ws, size_t ws_bytes,
                                    void* stream) {
-  if (N < 0 || H < 1 || D < 1 || M < 1) return MOGA_ERR_INVALID_ARG;
-  if (!(softmax_scale > 0.f) || !(softmax_scale < INFINITY)) return MOGA_ERR_INVALID_ARG;
-  if (dtype != MOGA_F32 && dtype != MOGA_BF16) return MOGA_ERR_UNSUPPORTED;
-  if (M > MOGA_MAX_GROUPS || N >= ((int64_t)1 << 31)) return MOGA_ERR_UNSUPPORTED;
-  if (dtype == MOGA_BF16 && D != 128) return MOGA_ERR_UNSUPPORTED;
-  if (dtype == MOGA_F32 && D != 64) return MOGA_ERR_UNSUPPORTED;
+  const int bad = check_attn_bwd_args(N, N, H, D, M, softmax_scale, dtype);
+  if (bad) return bad;
+  if (M > MOGA_MAX_GROUPS) return MOGA_ERR_UNSUPPORTED;
   if (N == 0) return MOGA_OK;
   if (!d_oh || !qh || !kh || !vh || !oh || !lse || !cu_seqlens || !d_qh || !d_kh || !d_vh)
     return MOGA_ERR_INVALID_ARG;
@@ -201,42 +277,42 @@ extern "C" int moga_group_attn_bwd(const void* d_oh, const void* qh, const void*
     return MOGA_ERR_INVALID_ARG;
   const size_t need = moga_attn_bwd_ws_bytes(N, H, D, dtype);
   if (!ws || ws_bytes < need) return MOGA_ERR_WORKSPACE;
+  return launch_attn_bwd(d_oh, qh, kh, vh, oh, lse, dtype, N, N, H, cu_seqlens, cu_seqlens, nullptr,
+                         nullptr, M, softmax_scale, d_qh, d_kh, d_vh, (float*)ws, (hipStream_t)stream);
+}
+
+extern "C" size_t moga_varlen_attn_bwd_ws_bytes(int64_t Nq, int H, int G) {
+  if (Nq <= 0 || H < 1) return 0;
+  return round_up(2 * (size_t)Nq * (size_t)H * sizeof(float), 16) + 2 * ((size_t)G + 1) * sizeof(int32_t);
+}
+
+extern "C" int moga_varlen_attn_bwd(const void* d_oh, const void* qh, const void* kh, const void* vh,
+                                    const void* oh, const float* lse, int dtype, int64_t Nq,
+                                    int64_t Nk, int H, int D, const int32_t* cu_seqlens_q,
+                                    const int32_t* cu_seqlens_k, int G, float softmax_scale,
+                                    void* d_qh, void* d_kh, void* d_vh, void* ws, size_t ws_bytes,
+                                    void* stream) {
+  const int bad = check_attn_bwd_args(Nq, Nk, H, D, G, softmax_scale, dtype);
+  if (bad) return bad;
+  if (G > MOGA_MAX_SEGMENTS) return MOGA_ERR_UNSUPPORTED;
+  if (Nq == 0 && Nk == 0) return MOGA_OK;
+  if (!cu_seqlens_q || !cu_seqlens_k) return MOGA_ERR_INVALID_ARG;
+  if (Nq > 0 && (!d_oh || !qh || !oh || !lse || !d_qh)) return MOGA_ERR_INVALID_ARG;
+  if (Nk > 0 && (!kh || !vh || !d_kh || !d_vh)) return MOGA_ERR_INVALID_ARG;
+  if (!(aligned16(d_oh) && aligned16(qh) && aligned16(kh) && aligned16(vh) && aligned16(oh) &&
+        aligned16(d_qh) && aligned16(d_kh) && aligned16(d_vh)))
+    return MOGA_ERR_INVALID_ARG;
   hipStream_t st = (hipStream_t)stream;
-  float* delta = (float*)ws;
-  const int64_t rows = N * (int64_t)H;
-  if (dtype == MOGA_BF16) {
-    float* lse2 = delta + rows;   // holds -lse/scale; `delta` holds -delta
-    attn_bwd_delta_kernel<16, true><<<(unsigned)((rows * 16 + 255) / 256), 256, 0, st>>>(
-        (const uintx4_t*)d_oh, (const uintx4_t*)oh, lse, rows, 1.f / softmax_scale, delta, lse2);
-    {
-      const int64_t tiles = max_tiles(N, M, 128);
-      const int64_t blocks = (tiles * H + 7) / 8 * 8;
-      if (blocks >= ((int64_t)1 << 31)) return MOGA_ERR_UNSUPPORTED;
-      attn_bwd_dkdv_pipe_kernel<4><<<(unsigned)blocks, 256, 0, st>>>(
-          (const unsigned short*)d_oh, (const unsigned short*)qh, (const unsigned short*)kh,
-          (const unsigned short*)vh, lse2, delta, cu_seqlens, M, N, H, softmax_scale, (int)tiles,
-          (unsigned short*)d_kh, (unsigned short*)d_vh);
-    }
-    {
-      const int64_t tiles = max_tiles(N, M, 256);
-      const int64_t blocks = (tiles * H + 7) / 8 * 8;
-      attn_bwd_dq_pipe_kernel<8, 1><<<(unsigned)blocks, 512, 0, st>>>(
-          (const unsigned short*)d_oh, (const unsigned short*)qh, (const unsigned short*)kh,
-          (const unsigned short*)vh, lse2, delta, cu_seqlens, M, N, H, softmax_scale, (int)tiles,
-          (unsigned short*)d_qh);
-    }
-  } else {
-    attn_bwd_delta_kernel<16, false><<<(unsigned)((rows * 16 + 255) / 256), 256, 0, st>>>(
-        (const uintx4_t*)d_oh, (const uintx4_t*)oh, lse, rows, 1.f, delta, nullptr);
-    const int64_t tiles = max_tiles(N, M, kF32BM);
-    const int64_t blocks = tiles * H;
-    if (blocks >= ((int64_t)1 << 31)) return MOGA_ERR_UNSUPPORTED;
-    attn_bwd_dkdv_f32_kernel<64><<<(unsigned)blocks, 64, 0, st>>>(
-        (const float*)d_oh, (const float*)qh, (const float*)kh, (const float*)vh, lse, delta,
-        cu_seqlens, M, N, H, softmax_scale, (int)tiles, (float*)d_kh, (float*)d_vh);
-    attn_bwd_dq_f32_kernel<64><<<(unsigned)blocks, 64, 0, st>>>(
-        (const float*)d_oh, (const float*)qh, (const float*)kh, (const float*)vh, lse, delta,
-        cu_seqlens, M, N, H, softmax_scale, (int)tiles, (float*)d_qh);
+  if (Nq == 0) {   // keys without any query: zero gradients
+    const int64_t nf = Nk * (int64_t)H * D / (dtype == MOGA_BF16 ? 2 : 1);
+    fill_zero_kernel<<<(unsigned)((nf + 255) / 256), 256, 0, st>>>((float*)d_kh, nf);
+    fill_zero_kernel<<<(unsigned)((nf + 255) / 256), 256, 0, st>>>((float*)d_vh, nf);
+    return launch_status();
   }
-  return launch_status();
+  const size_t need = moga_varlen_attn_bwd_ws_bytes(Nq, H, G);
+  if (!ws || ws_bytes < need || !aligned16(ws)) return MOGA_ERR_WORKSPACE;
+  int32_t* ts_q = (int32_t*)((char*)ws + round_up(2 * (size_t)Nq * (size_t)H * sizeof(float), 16));
+  int32_t* ts_k = ts_q + (G + 1);
+  return launch_attn_bwd(d_oh, qh, kh, vh, oh, lse, dtype, Nq, Nk, H, cu_seqlens_q, cu_seqlens_k, ts_q,
+                         ts_k, G, softmax_scale, d_qh, d_kh, d_vh, (float*)ws, st);
 }

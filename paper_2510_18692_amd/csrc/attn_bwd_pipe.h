@@ -155,7 +155,8 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_pipe_kernel(
     const unsigned short* __restrict__ d_oh, const unsigned short* __restrict__ qh,
     const unsigned short* __restrict__ kh, const unsigned short* __restrict__ vh,
     const float* __restrict__ neg_lse_over_scale, const float* __restrict__ neg_delta,
-    const int32_t* __restrict__ cu_seqlens, int M, int64_t N, int H, float scale,
+    const int32_t* __restrict__ cu_q, const int32_t* __restrict__ cu_k,
+    const int32_t* __restrict__ tile_start, int M, int64_t Nq, int64_t Nk, int H, float scale,
     int tiles_per_head, unsigned short* __restrict__ d_qh) {
   constexpr int BM = NW * 32 * QW;
   constexpr int kDmaPerTile = 2 * (16 / NW);
@@ -170,14 +171,34 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_pipe_kernel(
   const int head = (int)(work / tiles_per_head);
   const int tile = (int)(work - (int64_t)head * tiles_per_head);
   TileInfo ti;
-  if (!find_tile(cu_seqlens, M, BM, tile, s_start, &s_found, ti)) return;
-  const int gs = ti.row_begin, ge = ti.row_end, q0 = ti.tile_row;
-  const int n = ge - gs;
+  if (tile_start) {
+    if (!find_tile_presummed(tile_start, cu_q, M, BM, tile, ti)) return;
+  } else if (!find_tile(cu_q, M, BM, tile, s_start, &s_found, ti)) {
+    return;
+  }
+  const int ge = ti.row_end, q0 = ti.tile_row;   // query rows of the group end at ge
+  const int gs = cu_k[ti.group];                 // first key row of the group
+  const int n = cu_k[ti.group + 1] - gs;         // number of keys
 
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int r = lane & 31, h = lane >> 5;
-  const int64_t head_off = (int64_t)head * N;
+  const int64_t head_off = (int64_t)head * Nq;
+  const int64_t head_off_k = (int64_t)head * Nk;
   const float c = scale * 1.4426950408889634f;
+
+  if (n <= 0) {   // queries without keys: zero gradient (block-uniform branch)
+#pragma unroll
+    for (int qw = 0; qw < QW; ++qw) {
+      const int qrow = q0 + (wave * QW + qw) * 32 + r;
+      if (qrow < ge) {
+        uintx4_t* op = (uintx4_t*)(d_qh + (head_off + qrow) * kHeadDim + 64 * h);
+        const uintx4_t z = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) op[i] = z;
+      }
+    }
+    return;
+  }
 
   bf16x8_t qf[QW][8], dof[QW][8];
   float lq[QW], dl[QW];
@@ -197,8 +218,8 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_pipe_kernel(
   }
 
   PipeDma dma;
-  dma.kbase = uniform_ptr(kh + (head_off + gs) * kHeadDim);
-  dma.vbase = uniform_ptr(vh + (head_off + gs) * kHeadDim);
+  dma.kbase = uniform_ptr(kh + (head_off_k + gs) * kHeadDim);
+  dma.vbase = uniform_ptr(vh + (head_off_k + gs) * kHeadDim);
   dma.lds_k = lds_addr_uniform(&Ks[0][0]) + wave * 1024;
   dma.lds_v = lds_addr_uniform(&Vs[0][0]) + wave * 1024;
   dma.row0 = 4 * wave + (lane >> 4);
@@ -390,7 +411,8 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_pipe_kernel(
     const unsigned short* __restrict__ d_oh, const unsigned short* __restrict__ qh,
     const unsigned short* __restrict__ kh, const unsigned short* __restrict__ vh,
     const float* __restrict__ neg_lse_over_scale, const float* __restrict__ neg_delta,
-    const int32_t* __restrict__ cu_seqlens, int M, int64_t N, int H, float scale,
+    const int32_t* __restrict__ cu_q, const int32_t* __restrict__ cu_k,
+    const int32_t* __restrict__ tile_start, int M, int64_t Nq, int64_t Nk, int H, float scale,
     int tiles_per_head, unsigned short* __restrict__ d_kh, unsigned short* __restrict__ d_vh) {
   constexpr int BK = NW * 32;
   constexpr int kDmaPerTile = 2 * (16 / NW) + 2;
@@ -406,15 +428,33 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_pipe_kernel(
   if (work >= total) return;
   const int head = (int)(work / tiles_per_head);
   const int tile = (int)(work - (int64_t)head * tiles_per_head);
-  TileInfo ti;
-  if (!find_tile(cu_seqlens, M, BK, tile, s_start, &s_found, ti)) return;
-  const int gs = ti.row_begin, ge = ti.row_end, k0 = ti.tile_row;
-  const int n = ge - gs;
+  TileInfo ti;   // tiles run over the key rows of the groups
+  if (tile_start) {
+    if (!find_tile_presummed(tile_start, cu_k, M, BK, tile, ti)) return;
+  } else if (!find_tile(cu_k, M, BK, tile, s_start, &s_found, ti)) {
+    return;
+  }
+  const int ge = ti.row_end, k0 = ti.tile_row;   // key rows of the group end at ge
+  const int gs = cu_q[ti.group];                 // first query row of the group
+  const int n = cu_q[ti.group + 1] - gs;         // number of queries
 
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int r = lane & 31, h = lane >> 5;
-  const int64_t head_off = (int64_t)head * N;
+  const int64_t head_off = (int64_t)head * Nk;    // key-side tensors (kh, vh, d_kh, d_vh)
+  const int64_t head_off_q = (int64_t)head * Nq;  // query-side tensors (qh, d_oh, lse, delta)
   const float c = scale * 1.4426950408889634f;
+
+  if (n <= 0) {   // keys without queries: zero gradient (block-uniform branch)
+    const int krow = k0 + wave * 32 + r;
+    if (krow < ge) {
+      uintx4_t* dk4 = (uintx4_t*)(d_kh + (head_off + krow) * kHeadDim + 64 * h);
+      uintx4_t* dv4 = (uintx4_t*)(d_vh + (head_off + krow) * kHeadDim + 64 * h);
+      const uintx4_t z = {0u, 0u, 0u, 0u};
+#pragma unroll
+      for (int i = 0; i < 8; ++i) { dk4[i] = z; dv4[i] = z; }
+    }
+    return;
+  }
 
   // K, V fragments of this wave's 32 key rows: B operand, lane (r, h) holds row r, d = 16*ks + 8*h + 0..7
   const int krow = k0 + wave * 32 + r;
@@ -431,15 +471,15 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_pipe_kernel(
   }
 
   PipeDma dma;   // "k" = Q rows, "v" = dO rows of this head's group
-  dma.kbase = uniform_ptr(qh + (head_off + gs) * kHeadDim);
-  dma.vbase = uniform_ptr(d_oh + (head_off + gs) * kHeadDim);
+  dma.kbase = uniform_ptr(qh + (head_off_q + gs) * kHeadDim);
+  dma.vbase = uniform_ptr(d_oh + (head_off_q + gs) * kHeadDim);
   dma.lds_k = lds_addr_uniform(&Qs[0][0]) + wave * 1024;
   dma.lds_v = lds_addr_uniform(&dOs[0][0]) + wave * 1024;
   dma.row0 = 4 * wave + (lane >> 4);
   dma.chunk_off = (unsigned)(((lane & 15) ^ lds_swizzle(dma.row0)) * 16);
   dma.last_row = n - 1;
-  const void* lbase = uniform_ptr(neg_lse_over_scale + head_off + gs);
-  const void* dbase = uniform_ptr(neg_delta + head_off + gs);
+  const void* lbase = uniform_ptr(neg_lse_over_scale + head_off_q + gs);
+  const void* dbase = uniform_ptr(neg_delta + head_off_q + gs);
   const unsigned lds_l = lds_addr_uniform(&Ls[0][0]), lds_d = lds_addr_uniform(&Ds[0][0]);
   // every wave issues the (identical) 64-float lse / delta loads so that all waves count alike
   auto issue_tile = [&](int T) {

@@ -53,6 +53,54 @@ __device__ __forceinline__ bool find_tile(const int32_t* __restrict__ cu_seqlens
   return true;
 }
 
+// The same lookup for calls with many groups: `tile_start[g]` (M + 1 entries, written by
+// tile_start_kernel) is the flat index of group g's first tile; every thread binary-searches it.
+__device__ __forceinline__ bool find_tile_presummed(const int32_t* __restrict__ tile_start,
+                                                    const int32_t* __restrict__ cu_seqlens, int M,
+                                                    int rows_per_tile, int tile, TileInfo& out) {
+  if (tile >= tile_start[M]) return false;
+  int lo = 0, hi = M;   // invariant: tile_start[lo] <= tile < tile_start[hi]
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (tile_start[mid] <= tile) lo = mid; else hi = mid;
+  }
+  out.group = lo;
+  out.row_begin = cu_seqlens[lo];
+  out.row_end = cu_seqlens[lo + 1];
+  out.tile_row = out.row_begin + (tile - tile_start[lo]) * rows_per_tile;
+  return true;
+}
+
+// One block: exclusive scan of ceil(n_g / rows_per_tile) over the groups, M + 1 results.
+static __global__ __launch_bounds__(1024) void tile_start_kernel(const int32_t* __restrict__ cu_seqlens, int M,
+                                                                 int rows_per_tile, int32_t* __restrict__ tile_start) {
+  __shared__ int s_wave[16];
+  __shared__ int s_carry;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (threadIdx.x == 0) s_carry = 0;
+  __syncthreads();
+  for (int g0 = 0; g0 < M; g0 += 1024) {
+    const int g = g0 + threadIdx.x;
+    const int n = g < M ? cu_seqlens[g + 1] - cu_seqlens[g] : 0;
+    const int t = n > 0 ? (n + rows_per_tile - 1) / rows_per_tile : 0;
+    int incl = t;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int up = __shfl_up(incl, o, kWave);
+      if (lane >= o) incl += up;
+    }
+    if (lane == 63) s_wave[wave] = incl;
+    __syncthreads();
+    int before = s_carry;
+    for (int w = 0; w < wave; ++w) before += s_wave[w];
+    if (g < M) tile_start[g] = before + incl - t;
+    __syncthreads();
+    if (threadIdx.x == 1023) s_carry = before + incl;
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) tile_start[M] = s_carry;
+}
+
 // Upper bound on the number of tiles for N rows in M groups (host side).
 inline int64_t max_tiles(int64_t N, int M, int rows_per_tile) {
   return (N + rows_per_tile - 1) / rows_per_tile + M;

@@ -23,7 +23,8 @@ constexpr int kF32BM = 64, kF32BN = 32;
 template <int D>
 __global__ __launch_bounds__(64) void attn_fwd_f32_kernel(
     const float* __restrict__ qh, const float* __restrict__ kh, const float* __restrict__ vh,
-    const int32_t* __restrict__ cu_seqlens, int M, int64_t N, int H, float scale,
+    const int32_t* __restrict__ cu_q, const int32_t* __restrict__ cu_k,
+    const int32_t* __restrict__ tile_start, int M, int64_t Nq, int64_t Nk, int H, float scale,
     int tiles_per_head, float* __restrict__ oh, float* __restrict__ lse) {
   __shared__ __attribute__((aligned(16))) float Ks[kF32BN][D];
   __shared__ __attribute__((aligned(16))) float Vs[kF32BN][D];
@@ -32,9 +33,15 @@ __global__ __launch_bounds__(64) void attn_fwd_f32_kernel(
   const int head = blockIdx.x / tiles_per_head;
   const int tile = blockIdx.x - head * tiles_per_head;
   TileInfo ti;
-  if (!find_tile(cu_seqlens, M, kF32BM, tile, s_start, &s_found, ti)) return;
+  if (tile_start) {
+    if (!find_tile_presummed(tile_start, cu_q, M, kF32BM, tile, ti)) return;
+  } else if (!find_tile(cu_q, M, kF32BM, tile, s_start, &s_found, ti)) {
+    return;
+  }
   const int ge = ti.row_end;
-  const int64_t head_off = (int64_t)head * N;
+  const int kbeg = cu_k[ti.group], kend = cu_k[ti.group + 1];   // key rows of the group
+  const int64_t head_off = (int64_t)head * Nq;
+  const int64_t head_off_k = (int64_t)head * Nk;
   const int row = ti.tile_row + threadIdx.x;
   const bool valid = row < ge;
   const float* qp = qh + (head_off + (valid ? row : ge - 1)) * D;
@@ -48,20 +55,20 @@ __global__ __launch_bounds__(64) void attn_fwd_f32_kernel(
   for (int cI = 0; cI < D; ++cI) o[cI] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
 
-  for (int kv0 = ti.row_begin; kv0 < ge; kv0 += kF32BN) {
+  for (int kv0 = kbeg; kv0 < kend; kv0 += kF32BN) {
     __syncthreads();
     for (int idx = threadIdx.x; idx < kF32BN * (D / 4); idx += 64) {
       const int rr = idx / (D / 4), c4 = (idx - rr * (D / 4)) * 4;
       floatx4_t kk = {0.f, 0.f, 0.f, 0.f}, vv = {0.f, 0.f, 0.f, 0.f};
-      if (kv0 + rr < ge) {
-        kk = *(const floatx4_t*)(kh + (head_off + kv0 + rr) * D + c4);
-        vv = *(const floatx4_t*)(vh + (head_off + kv0 + rr) * D + c4);
+      if (kv0 + rr < kend) {
+        kk = *(const floatx4_t*)(kh + (head_off_k + kv0 + rr) * D + c4);
+        vv = *(const floatx4_t*)(vh + (head_off_k + kv0 + rr) * D + c4);
       }
       *(floatx4_t*)&Ks[rr][c4] = kk;
       *(floatx4_t*)&Vs[rr][c4] = vv;
     }
     __syncthreads();
-    const int nk = min(kF32BN, ge - kv0);
+    const int nk = min(kF32BN, kend - kv0);
     float s[kF32BN];
     float mx = -INFINITY;
 #pragma unroll
@@ -99,14 +106,14 @@ __global__ __launch_bounds__(64) void attn_fwd_f32_kernel(
     }
   }
   if (valid) {
-    const float inv = 1.f / l_run;
+    const float inv = l_run > 0.f ? 1.f / l_run : 0.f;   // no keys: zero output, lse = -inf
     float* op = oh + (head_off + row) * D;
 #pragma unroll
     for (int cI = 0; cI < D; cI += 4) {
       floatx4_t t = {o[cI] * inv, o[cI + 1] * inv, o[cI + 2] * inv, o[cI + 3] * inv};
       *(floatx4_t*)(op + cI) = t;
     }
-    lse[head_off + row] = m_run + logf(l_run);
+    lse[head_off + row] = l_run > 0.f ? m_run + logf(l_run) : -INFINITY;
   }
 }
 
@@ -114,40 +121,72 @@ __global__ __launch_bounds__(64) void attn_fwd_f32_kernel(
 
 using namespace moga;
 
+// Shared launcher.  tile_start == NULL: tile lookup inside the kernels (M <= MOGA_MAX_GROUPS).
+static int launch_attn_fwd(const void* qh, const void* kh, const void* vh, int dtype, int64_t Nq,
+                           int64_t Nk, int H, int D, const int32_t* cu_q, const int32_t* cu_k,
+                           int32_t* tile_start, int M, float softmax_scale, void* oh, float* lse,
+                           hipStream_t st) {
+  const int bm = dtype == MOGA_BF16 ? 256 : kF32BM;
+  const int64_t tiles = max_tiles(Nq, M, bm);
+  const int64_t blocks = dtype == MOGA_BF16 ? (tiles * H + 7) / 8 * 8 : tiles * H;
+  if (blocks >= ((int64_t)1 << 31)) return MOGA_ERR_UNSUPPORTED;
+  if (tile_start) tile_start_kernel<<<1, 1024, 0, st>>>(cu_q, M, bm, tile_start);
+  if (dtype == MOGA_BF16) {
+    attn_fwd_bf16_pipe_kernel<8, 1><<<(unsigned)blocks, 512, 0, st>>>(
+        (const unsigned short*)qh, (const unsigned short*)kh, (const unsigned short*)vh, cu_q, cu_k,
+        tile_start, M, Nq, Nk, H, softmax_scale, (int)tiles, (unsigned short*)oh, lse);
+  } else if (D == 64) {
+    attn_fwd_f32_kernel<64><<<(unsigned)blocks, 64, 0, st>>>(
+        (const float*)qh, (const float*)kh, (const float*)vh, cu_q, cu_k, tile_start, M, Nq, Nk, H,
+        softmax_scale, (int)tiles, (float*)oh, lse);
+  } else {
+    attn_fwd_f32_kernel<128><<<(unsigned)blocks, 64, 0, st>>>(
+        (const float*)qh, (const float*)kh, (const float*)vh, cu_q, cu_k, tile_start, M, Nq, Nk, H,
+        softmax_scale, (int)tiles, (float*)oh, lse);
+  }
+  return launch_status();
+}
+
+static int check_attn_args(int64_t Nq, int64_t Nk, int H, int D, int M, float softmax_scale, int dtype) {
+  if (Nq < 0 || Nk < 0 || H < 1 || D < 1 || M < 1) return MOGA_ERR_INVALID_ARG;
+  if (!(softmax_scale > 0.f) || !(softmax_scale < INFINITY)) return MOGA_ERR_INVALID_ARG;
+  if (dtype != MOGA_F32 && dtype != MOGA_BF16) return MOGA_ERR_UNSUPPORTED;
+  if (Nq >= ((int64_t)1 << 31) || Nk >= ((int64_t)1 << 31)) return MOGA_ERR_UNSUPPORTED;
+  if (dtype == MOGA_BF16 && D != 128) return MOGA_ERR_UNSUPPORTED;
+  if (dtype == MOGA_F32 && D != 64 && D != 128) return MOGA_ERR_UNSUPPORTED;
+  return MOGA_OK;
+}
+
 extern "C" int moga_group_attn_fwd(const void* qh, const void* kh, const void* vh, int dtype,
                                    int64_t N, int H, int D, const int32_t* cu_seqlens, int M,
                                    float softmax_scale, void* oh, float* lse, void* ws,
                                    size_t ws_bytes, void* stream) {
   (void)ws; (void)ws_bytes;
-  if (N < 0 || H < 1 || D < 1 || M < 1) return MOGA_ERR_INVALID_ARG;
-  if (!(softmax_scale > 0.f) || !(softmax_scale < INFINITY)) return MOGA_ERR_INVALID_ARG;
-  if (dtype != MOGA_F32 && dtype != MOGA_BF16) return MOGA_ERR_UNSUPPORTED;
-  if (M > MOGA_MAX_GROUPS || N >= ((int64_t)1 << 31)) return MOGA_ERR_UNSUPPORTED;
-  if (dtype == MOGA_BF16 && D != 128) return MOGA_ERR_UNSUPPORTED;
-  if (dtype == MOGA_F32 && D != 64 && D != 128) return MOGA_ERR_UNSUPPORTED;
+  const int bad = check_attn_args(N, N, H, D, M, softmax_scale, dtype);
+  if (bad) return bad;
+  if (M > MOGA_MAX_GROUPS) return MOGA_ERR_UNSUPPORTED;
   if (N == 0) return MOGA_OK;
   if (!qh || !kh || !vh || !cu_seqlens || !oh || !lse) return MOGA_ERR_INVALID_ARG;
   if (!(aligned16(qh) && aligned16(kh) && aligned16(vh) && aligned16(oh))) return MOGA_ERR_INVALID_ARG;
-  hipStream_t st = (hipStream_t)stream;
-  if (dtype == MOGA_BF16) {
-    const int64_t tiles = max_tiles(N, M, 256);
-    const int64_t blocks = (tiles * H + 7) / 8 * 8;
-    if (blocks >= ((int64_t)1 << 31)) return MOGA_ERR_UNSUPPORTED;
-    attn_fwd_bf16_pipe_kernel<8, 1><<<(unsigned)blocks, 512, 0, st>>>(
-        (const unsigned short*)qh, (const unsigned short*)kh, (const unsigned short*)vh, cu_seqlens, M,
-        N, H, softmax_scale, (int)tiles, (unsigned short*)oh, lse);
-  } else {
-    const int64_t tiles = max_tiles(N, M, kF32BM);
-    const int64_t blocks = tiles * H;
-    if (blocks >= ((int64_t)1 << 31)) return MOGA_ERR_UNSUPPORTED;
-    if (D == 64)
-      attn_fwd_f32_kernel<64><<<(unsigned)blocks, 64, 0, st>>>(
-          (const float*)qh, (const float*)kh, (const float*)vh, cu_seqlens, M, N, H,
-          softmax_scale, (int)tiles, (float*)oh, lse);
-    else
-      attn_fwd_f32_kernel<128><<<(unsigned)blocks, 64, 0, st>>>(
-          (const float*)qh, (const float*)kh, (const float*)vh, cu_seqlens, M, N, H,
-          softmax_scale, (int)tiles, (float*)oh, lse);
-  }
-  return launch_status();
+  return launch_attn_fwd(qh, kh, vh, dtype, N, N, H, D, cu_seqlens, cu_seqlens, nullptr, M,
+                         softmax_scale, oh, lse, (hipStream_t)stream);
+}
+
+extern "C" size_t moga_varlen_attn_fwd_ws_bytes(int G) { return ((size_t)G + 1) * sizeof(int32_t); }
+
+extern "C" int moga_varlen_attn_fwd(const void* qh, const void* kh, const void* vh, int dtype,
+                                    int64_t Nq, int64_t Nk, int H, int D,
+                                    const int32_t* cu_seqlens_q, const int32_t* cu_seqlens_k, int G,
+                                    float softmax_scale, void* oh, float* lse, void* ws,
+                                    size_t ws_bytes, void* stream) {
+  const int bad = check_attn_args(Nq, Nk, H, D, G, softmax_scale, dtype);
+  if (bad) return bad;
+  if (G > MOGA_MAX_SEGMENTS) return MOGA_ERR_UNSUPPORTED;
+  if (Nq == 0) return MOGA_OK;
+  if (!qh || !cu_seqlens_q || !cu_seqlens_k || !oh || !lse) return MOGA_ERR_INVALID_ARG;
+  if (Nk > 0 && (!kh || !vh)) return MOGA_ERR_INVALID_ARG;
+  if (!(aligned16(qh) && aligned16(kh) && aligned16(vh) && aligned16(oh))) return MOGA_ERR_INVALID_ARG;
+  if (!ws || ws_bytes < moga_varlen_attn_fwd_ws_bytes(G)) return MOGA_ERR_WORKSPACE;
+  return launch_attn_fwd(qh, kh, vh, dtype, Nq, Nk, H, D, cu_seqlens_q, cu_seqlens_k, (int32_t*)ws, G,
+                         softmax_scale, oh, lse, (hipStream_t)stream);
 }

@@ -162,11 +162,16 @@ __device__ __forceinline__ void pipe_issue_tile(const PipeDma& d, int kv0, int b
   }
 }
 
+// Queries are the rows cu_q[g] .. cu_q[g+1] of qh [H, Nq, 128]; their keys and values the rows
+// cu_k[g] .. cu_k[g+1] of kh, vh [H, Nk, 128] (cu_k == cu_q and Nk == Nq for MoGA's groups).
+// tile_start: NULL (tile lookup from cu_q inside the block, M <= MOGA_MAX_GROUPS) or the
+// pre-summed first-tile index of every group.
 template <int NW, int QW>
 __global__ __launch_bounds__(NW * 64) void attn_fwd_bf16_pipe_kernel(
     const unsigned short* __restrict__ qh, const unsigned short* __restrict__ kh,
-    const unsigned short* __restrict__ vh, const int32_t* __restrict__ cu_seqlens, int M,
-    int64_t N, int H, float scale, int tiles_per_head, unsigned short* __restrict__ oh,
+    const unsigned short* __restrict__ vh, const int32_t* __restrict__ cu_q,
+    const int32_t* __restrict__ cu_k, const int32_t* __restrict__ tile_start, int M,
+    int64_t Nq, int64_t Nk, int H, float scale, int tiles_per_head, unsigned short* __restrict__ oh,
     float* __restrict__ lse) {
   constexpr int BM = NW * 32 * QW;
   constexpr int kDmaPerTile = 2 * (16 / NW);   // direct-to-LDS instructions per thread per tile
@@ -182,15 +187,36 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_bf16_pipe_kernel(
   const int head = (int)(work / tiles_per_head);
   const int tile = (int)(work - (int64_t)head * tiles_per_head);
   TileInfo ti;
-  if (!find_tile(cu_seqlens, M, BM, tile, s_start, &s_found, ti)) return;
-  const int gs = ti.row_begin, ge = ti.row_end, q0 = ti.tile_row;
-  const int n = ge - gs;
+  if (tile_start) {
+    if (!find_tile_presummed(tile_start, cu_q, M, BM, tile, ti)) return;
+  } else if (!find_tile(cu_q, M, BM, tile, s_start, &s_found, ti)) {
+    return;
+  }
+  const int ge = ti.row_end, q0 = ti.tile_row;   // query rows of the group end at ge
+  const int gs = cu_k[ti.group];                 // first key row of the group
+  const int n = cu_k[ti.group + 1] - gs;         // number of keys
 
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int r = lane & 31, h = lane >> 5;
-  const int64_t head_off = (int64_t)head * N;
+  const int64_t head_off = (int64_t)head * Nq;
+  const int64_t head_off_k = (int64_t)head * Nk;
   const float c = scale * 1.4426950408889634f;
   const float tau = 8.f / c;
+
+  if (n <= 0) {   // queries without keys: zero output, lse = -inf (block-uniform branch)
+#pragma unroll
+    for (int qw = 0; qw < QW; ++qw) {
+      const int qrow = q0 + (wave * QW + qw) * 32 + r;
+      if (qrow < ge) {
+        uintx4_t* op = (uintx4_t*)(oh + (head_off + qrow) * kHeadDim + 64 * h);
+        const uintx4_t z = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) op[i] = z;
+        if (h == 0) lse[head_off + qrow] = -INFINITY;
+      }
+    }
+    return;
+  }
 
   // ---- Q fragments (B operand): lane (r, h) holds Q[q = r][d = 16*ks + 8*h + 0..7]
   bf16x8_t qf[QW][8];
@@ -205,8 +231,8 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_bf16_pipe_kernel(
 
   // ---- direct-to-LDS loads: first kPipeAhead + 1 tiles (always issued; rows are clamped)
   PipeDma dma;
-  dma.kbase = uniform_ptr(kh + (head_off + gs) * kHeadDim);
-  dma.vbase = uniform_ptr(vh + (head_off + gs) * kHeadDim);
+  dma.kbase = uniform_ptr(kh + (head_off_k + gs) * kHeadDim);
+  dma.vbase = uniform_ptr(vh + (head_off_k + gs) * kHeadDim);
   dma.lds_k = lds_addr_uniform(&Ks[0][0]) + wave * 1024;
   dma.lds_v = lds_addr_uniform(&Vs[0][0]) + wave * 1024;
   dma.row0 = 4 * wave + (lane >> 4);
