@@ -190,6 +190,65 @@ int moga_varlen_attn_bwd(const void* d_oh, const void* qh, const void* kh, const
                          void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Static groups of Section 3.2 ("Spatial-Temporal Group Attention"), built on the HOST: the lists
+ * depend only on the latent grid (T frames of Hh x Ww tokens, token = (t*Hh + y)*Ww + x), the window
+ * (wh x ww, non-overlapping, ragged at the border), the run length tg (consecutive frames of one
+ * shot; the last run of a shot may be shorter) and the shot of every frame.  A group is
+ * (run, window); its queries are its own tokens; its keys are its own tokens followed by the tokens
+ * of the same window in the last a_prev frames of the previous shot and the first a_next frames of
+ * the next shot (the paper adds two latent frames from the adjacent shots: a_prev = a_next = 1).
+ * EVERY pointer of these two calls is a HOST pointer; shot_of_frame [T] must be non-decreasing.
+ *   moga_stga_index_sizes: *n_groups = G, *n_keys = Nk (total listed keys).
+ *   moga_stga_build_index: q_index [N] (queries of group g: q_index[cu_q[g] .. cu_q[g+1]), ascending),
+ *     q_slot [N] (inverse of q_index), cu_q [G+1], kv_index [Nk], cu_k [G+1], and for the backward
+ *     of the key gather inv_cu [N+1], inv_slots [Nk]: token t is listed at the key slots
+ *     inv_slots[inv_cu[t] .. inv_cu[t+1]), ascending.
+ * The per-frame groups of the same section need no lists: group f = frame f, cu[f] = f*Hh*Ww.
+ */
+int moga_stga_index_sizes(int T, int Hh, int Ww, int wh, int ww, int tg, const int32_t* shot_of_frame,
+                          int a_prev, int a_next, int64_t* n_groups, int64_t* n_keys);
+int moga_stga_build_index(int T, int Hh, int Ww, int wh, int ww, int tg, const int32_t* shot_of_frame,
+                          int a_prev, int a_next, int32_t* q_index, int32_t* q_slot, int32_t* cu_q,
+                          int32_t* kv_index, int32_t* cu_k, int32_t* inv_cu, int32_t* inv_slots);
+
+/*
+ * Gather through an index list (device pointers again): dst[h][j][:] = src[index[j]][h][:],
+ * src [N, H, D] token order, dst [H, Nk, D]; index [Nk] int32 with values in [0, N), repeats allowed.
+ */
+int moga_gather_rows(const void* src, int dtype, const int32_t* index, int64_t Nk, int H, int D,
+                     void* dst, void* stream);
+
+/*
+ * Backward of moga_gather_rows: d_src[t][h][:] (+)= sum of d_dst[h][j][:] over the slots j that
+ * list token t (inv_cu [N+1], inv_slots [Nk] as built by moga_stga_build_index); fp32 sums in
+ * ascending slot order, so the result is reproducible.  accumulate != 0 adds to d_src [N, H, D],
+ * otherwise d_src is overwritten (tokens listed nowhere get zero).
+ */
+int moga_gather_rows_bwd(const void* d_dst, int dtype, const int32_t* inv_cu, const int32_t* inv_slots,
+                         int64_t N, int64_t Nk, int H, int D, int accumulate, void* d_src, void* stream);
+
+/*
+ * Mean of the three branches of Section 3.2 fused into one scatter:
+ *   o[t][h][:] = ( gate[t] * a_moga[h][inv_moga[t]][:] + a_stga[h][inv_stga[t]][:]
+ *                  + a_frame[h][inv_frame[t]][:] ) / 3
+ * a_* are [H, N, D] in each branch's own row order; inv_* [N] maps a token to its row there
+ * (inv_perm of moga_permute, q_slot of moga_stga_build_index; NULL = identity).  Only the dynamic
+ * branch is gated (Eq. 5).  o [N, H, D].
+ */
+int moga_merge3_fwd(const void* a_moga, const void* a_stga, const void* a_frame, int dtype,
+                    const int32_t* inv_moga, const int32_t* inv_stga, const int32_t* inv_frame,
+                    const float* gate, int64_t N, int H, int D, void* o, void* stream);
+
+/*
+ * Backward of moga_merge3_fwd: d_a_moga[h][inv_moga[t]] = gate[t] * d_o[t][h] / 3,
+ * d_a_stga / d_a_frame likewise without the gate, d_gate[t] = sum_{h,c} d_o[t][h][c] * a_moga[h][inv_moga[t]][c] / 3.
+ */
+int moga_merge3_bwd(const void* d_o, const void* a_moga, int dtype, const int32_t* inv_moga,
+                    const int32_t* inv_stga, const int32_t* inv_frame, const float* gate,
+                    int64_t N, int H, int D, void* d_a_moga, void* d_a_stga, void* d_a_frame,
+                    float* d_gate, void* stream);
+
+/*
  * Group balancing loss, Eqs. 6-8 (Section 3.2; alpha = 0.1 in the paper's training setup):
  *   frac[i] = (1/N) #{x : group[x] = i}                   (Eq. 7)
  *   prob[i] = (1/N) sum_{x : group[x] = i} gate[x]        (Eq. 8: the sum runs over the tokens

@@ -42,6 +42,13 @@ _SIGNATURES = {
                                     _vp, _sz, _vp]),
     "moga_varlen_attn_bwd": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _i64, _i64, _i32, _i32, _vp, _vp, _i32,
                                     _f32, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "moga_stga_index_sizes": (_i32, [_i32, _i32, _i32, _i32, _i32, _i32, _vp, _i32, _i32, _vp, _vp]),
+    "moga_stga_build_index": (_i32, [_i32, _i32, _i32, _i32, _i32, _i32, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp,
+                                     _vp, _vp]),
+    "moga_gather_rows": (_i32, [_vp, _i32, _vp, _i64, _i32, _i32, _vp, _vp]),
+    "moga_gather_rows_bwd": (_i32, [_vp, _i32, _vp, _vp, _i64, _i64, _i32, _i32, _i32, _vp, _vp]),
+    "moga_merge3_fwd": (_i32, [_vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _vp]),
+    "moga_merge3_bwd": (_i32, [_vp, _vp, _i32, _vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp, _vp]),
     "moga_balance_loss": (_i32, [_vp, _vp, _i64, _i32, _f32, _vp, _vp, _vp, _vp, _sz, _vp]),
     "moga_balance_loss_bwd": (_i32, [_vp, _vp, _i64, _i32, _f32, _f32, _i32, _vp, _vp]),
 }
@@ -250,6 +257,74 @@ def moga_varlen_attn_bwd(d_oh, qh, kh, vh, oh, lse, cu_seqlens_q, cu_seqlens_k, 
                                      _p(d_kh), _p(d_vh), _p(ws), ws.numel(), _stream(stream))
     _check("moga_varlen_attn_bwd", st)
     return d_qh, d_kh, d_vh
+
+
+def moga_stga_build_index(T, Hh, Ww, wh, ww, tg, shot_of_frame, a_prev=1, a_next=1, device="cuda"):
+    """Static index lists (host builder), uploaded to `device` (None keeps them as numpy arrays)."""
+    import numpy as np
+    shots = np.ascontiguousarray(np.asarray(shot_of_frame, dtype=np.int32))
+    assert shots.shape == (T,)
+    G, Nk = ctypes.c_int64(0), ctypes.c_int64(0)
+    sp = shots.ctypes.data_as(ctypes.c_void_p)
+    st = load().moga_stga_index_sizes(T, Hh, Ww, wh, ww, tg, sp, a_prev, a_next, ctypes.byref(G), ctypes.byref(Nk))
+    _check("moga_stga_index_sizes", st)
+    N, G, Nk = T * Hh * Ww, G.value, Nk.value
+    out = {"q_index": np.empty(N, np.int32), "q_slot": np.empty(N, np.int32), "cu_q": np.empty(G + 1, np.int32),
+           "kv_index": np.empty(Nk, np.int32), "cu_k": np.empty(G + 1, np.int32),
+           "inv_cu": np.empty(N + 1, np.int32), "inv_slots": np.empty(Nk, np.int32)}
+    hp = lambda a: a.ctypes.data_as(ctypes.c_void_p)
+    st = load().moga_stga_build_index(T, Hh, Ww, wh, ww, tg, sp, a_prev, a_next, hp(out["q_index"]),
+                                      hp(out["q_slot"]), hp(out["cu_q"]), hp(out["kv_index"]), hp(out["cu_k"]),
+                                      hp(out["inv_cu"]), hp(out["inv_slots"]))
+    _check("moga_stga_build_index", st)
+    if device is not None:
+        out = {k: torch.from_numpy(v).to(device) for k, v in out.items()}
+    out["n_groups"], out["n_keys"] = G, Nk
+    return out
+
+
+def moga_gather_rows(src, index, stream=None):
+    """src [N, H, D], index [Nk] -> [H, Nk, D]"""
+    N, H, D = src.shape
+    Nk = index.shape[0]
+    dst = torch.empty((H, Nk, D), dtype=src.dtype, device=src.device)
+    st = load().moga_gather_rows(_p(src), _dt(src), _p(index), Nk, H, D, _p(dst), _stream(stream))
+    _check("moga_gather_rows", st)
+    return dst
+
+
+def moga_gather_rows_bwd(d_dst, inv_cu, inv_slots, N, d_src=None, stream=None):
+    """d_dst [H, Nk, D] -> d_src [N, H, D]; adds into `d_src` when given."""
+    H, Nk, D = d_dst.shape
+    accumulate = d_src is not None
+    if d_src is None:
+        d_src = torch.empty((N, H, D), dtype=d_dst.dtype, device=d_dst.device)
+    st = load().moga_gather_rows_bwd(_p(d_dst), _dt(d_dst), _p(inv_cu), _p(inv_slots), N, Nk, H, D,
+                                     int(accumulate), _p(d_src), _stream(stream))
+    _check("moga_gather_rows_bwd", st)
+    return d_src
+
+
+def moga_merge3_fwd(a_moga, a_stga, a_frame, inv_moga, inv_stga, inv_frame, gate, stream=None):
+    """Three [H, N, D] branch outputs -> their mean [N, H, D] in token order (dynamic branch gated)."""
+    H, N, D = a_moga.shape
+    o = torch.empty((N, H, D), dtype=a_moga.dtype, device=a_moga.device)
+    st = load().moga_merge3_fwd(_p(a_moga), _p(a_stga), _p(a_frame), _dt(a_moga), _p(inv_moga), _p(inv_stga),
+                                _p(inv_frame), _p(gate), N, H, D, _p(o), _stream(stream))
+    _check("moga_merge3_fwd", st)
+    return o
+
+
+def moga_merge3_bwd(d_o, a_moga, inv_moga, inv_stga, inv_frame, gate, stream=None):
+    """-> (d_a_moga, d_a_stga, d_a_frame [H, N, D], d_gate f32 [N])"""
+    N, H, D = d_o.shape
+    mk = lambda: torch.empty((H, N, D), dtype=d_o.dtype, device=d_o.device)
+    d_m, d_s, d_f = mk(), mk(), mk()
+    d_gate = torch.empty(N, dtype=torch.float32, device=d_o.device)
+    st = load().moga_merge3_bwd(_p(d_o), _p(a_moga), _dt(d_o), _p(inv_moga), _p(inv_stga), _p(inv_frame), _p(gate),
+                                N, H, D, _p(d_m), _p(d_s), _p(d_f), _p(d_gate), _stream(stream))
+    _check("moga_merge3_bwd", st)
+    return d_m, d_s, d_f, d_gate
 
 
 def moga_balance_loss(group, gate, M, alpha, stream=None):

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmoga.so")
-SOURCES = ["api.hip", "route.hip", "permute.hip", "attn_fwd.hip", "attn_bwd.hip", "balance.hip"]
+SOURCES = ["api.hip", "route.hip", "permute.hip", "attn_fwd.hip", "attn_bwd.hip", "balance.hip", "static_index.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=default",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 VALU ops

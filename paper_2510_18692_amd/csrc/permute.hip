@@ -316,6 +316,173 @@ __global__ __launch_bounds__(256) void unpermute_bwd_kernel(
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// Static branches (Section 3.2): gradient of a gather whose index lists a token several times,
+// and the mean of the dynamic branch and two static branches fused into one scatter.
+// ---------------------------------------------------------------------------------------
+template <bool BF16>
+__device__ __forceinline__ void add16(float (&acc)[8], uintx4_t v) {
+  if (BF16) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { acc[2 * i] += bf16_lo_to_f32(v[i]); acc[2 * i + 1] += bf16_hi_to_f32(v[i]); }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc[i] += __uint_as_float(v[i]);
+  }
+}
+
+template <bool BF16>
+__device__ __forceinline__ uintx4_t pack16(const float (&acc)[8]) {
+  uintx4_t r;
+  if (BF16) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r[i] = pack_bf16x2(acc[2 * i], acc[2 * i + 1]);
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r[i] = __float_as_uint(acc[i]);
+  }
+  return r;
+}
+
+// d_src[t][h] (+)= sum over the slots j that list token t (inv_slots[inv_cu[t] .. inv_cu[t+1]),
+// ascending) of d_dst[h][j]; fp32 sums in a fixed order.
+template <int LPR, bool BF16>
+__global__ __launch_bounds__(256) void gather_rows_bwd_kernel(
+    const uintx4_t* __restrict__ d_dst, const int32_t* __restrict__ inv_cu,
+    const int32_t* __restrict__ inv_slots, int64_t N, int64_t Nk, int H, int accumulate,
+    uintx4_t* __restrict__ d_src) {
+  constexpr int RPW = 64 / LPR;
+  constexpr int IT = kSlotsPerBlock / RPW;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int part = lane % LPR, rsub = lane / LPR;
+  const int64_t t0 = (int64_t)blockIdx.x * kSlotsPerBlock;
+  for (int it = 0; it < IT; ++it) {
+    const int64_t t = t0 + it * RPW + rsub;
+    if (t >= N) continue;
+    const int beg = inv_cu[t], end = inv_cu[t + 1];
+    for (int h = wave; h < H; h += 4) {
+      float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      uintx4_t* dp = d_src + (t * H + h) * LPR + part;
+      if (accumulate) add16<BF16>(acc, *dp);
+      for (int j = beg; j < end; ++j)
+        add16<BF16>(acc, d_dst[((int64_t)h * Nk + inv_slots[j]) * LPR + part]);
+      *dp = pack16<BF16>(acc);
+    }
+  }
+}
+
+// o[t][h] = alpha * (gate[t] * a_m[h][inv_m[t]] + a_s[h][inv_s[t]] + a_f[h][inv_f[t]]); a NULL
+// inverse list means the identity (the branch keeps token order).
+template <int LPR, bool BF16>
+__global__ __launch_bounds__(256) void merge3_fwd_kernel(
+    const uintx4_t* __restrict__ a_m, const uintx4_t* __restrict__ a_s, const uintx4_t* __restrict__ a_f,
+    const int32_t* __restrict__ inv_m, const int32_t* __restrict__ inv_s, const int32_t* __restrict__ inv_f,
+    const float* __restrict__ gate, float alpha, int64_t N, int H, uintx4_t* __restrict__ o) {
+  constexpr int RPW = 64 / LPR;
+  constexpr int IT = kSlotsPerBlock / RPW;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int part = lane % LPR, rsub = lane / LPR;
+  const int64_t t0 = (int64_t)blockIdx.x * kSlotsPerBlock;
+  int64_t jm[IT], js[IT], jf[IT];
+  float g[IT];
+  bool ok[IT];
+#pragma unroll
+  for (int it = 0; it < IT; ++it) {
+    const int64_t t = t0 + it * RPW + rsub;
+    ok[it] = t < N;
+    jm[it] = ok[it] ? (inv_m ? inv_m[t] : t) : 0;
+    js[it] = ok[it] ? (inv_s ? inv_s[t] : t) : 0;
+    jf[it] = ok[it] ? (inv_f ? inv_f[t] : t) : 0;
+    g[it] = ok[it] ? gate[t] : 0.f;
+  }
+  for (int h = wave; h < H; h += 4) {
+    uintx4_t vm[IT], vs[IT], vf[IT];
+#pragma unroll
+    for (int it = 0; it < IT; ++it)
+      if (ok[it]) {
+        vm[it] = a_m[((int64_t)h * N + jm[it]) * LPR + part];
+        vs[it] = a_s[((int64_t)h * N + js[it]) * LPR + part];
+        vf[it] = a_f[((int64_t)h * N + jf[it]) * LPR + part];
+      }
+#pragma unroll
+    for (int it = 0; it < IT; ++it)
+      if (ok[it]) {
+        float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        add16<BF16>(acc, vm[it]);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] *= g[it];
+        add16<BF16>(acc, vs[it]);
+        add16<BF16>(acc, vf[it]);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] *= alpha;
+        const int64_t t = t0 + it * RPW + rsub;
+        o[(t * H + h) * LPR + part] = pack16<BF16>(acc);
+      }
+  }
+}
+
+// Backward of merge3_fwd: d_m[h][inv_m[t]] = alpha * gate[t] * d_o[t][h], d_s / d_f = alpha * d_o[t][h],
+// d_gate[t] = alpha * sum_{h,c} d_o[t][h][c] * a_m[h][inv_m[t]][c].
+template <int LPR, bool BF16>
+__global__ __launch_bounds__(256) void merge3_bwd_kernel(
+    const uintx4_t* __restrict__ d_o, const uintx4_t* __restrict__ a_m,
+    const int32_t* __restrict__ inv_m, const int32_t* __restrict__ inv_s, const int32_t* __restrict__ inv_f,
+    const float* __restrict__ gate, float alpha, int64_t N, int H, uintx4_t* __restrict__ d_m,
+    uintx4_t* __restrict__ d_s, uintx4_t* __restrict__ d_f, float* __restrict__ d_gate) {
+  constexpr int RPW = 64 / LPR;
+  constexpr int IT = kSlotsPerBlock / RPW;
+  __shared__ float s_part[4][kSlotsPerBlock];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int part = lane % LPR, rsub = lane / LPR;
+  const int64_t t0 = (int64_t)blockIdx.x * kSlotsPerBlock;
+  int64_t jm[IT], js[IT], jf[IT];
+  float g[IT], acc[IT];
+  bool ok[IT];
+#pragma unroll
+  for (int it = 0; it < IT; ++it) {
+    const int64_t t = t0 + it * RPW + rsub;
+    ok[it] = t < N;
+    jm[it] = ok[it] ? (inv_m ? inv_m[t] : t) : 0;
+    js[it] = ok[it] ? (inv_s ? inv_s[t] : t) : 0;
+    jf[it] = ok[it] ? (inv_f ? inv_f[t] : t) : 0;
+    g[it] = ok[it] ? gate[t] * alpha : 0.f;
+    acc[it] = 0.f;
+  }
+  for (int h = wave; h < H; h += 4) {
+    uintx4_t a[IT], b[IT];
+#pragma unroll
+    for (int it = 0; it < IT; ++it)
+      if (ok[it]) {
+        const int64_t t = t0 + it * RPW + rsub;
+        a[it] = d_o[(t * H + h) * LPR + part];
+        b[it] = a_m[((int64_t)h * N + jm[it]) * LPR + part];
+      }
+#pragma unroll
+    for (int it = 0; it < IT; ++it)
+      if (ok[it]) {
+        acc[it] += dot16<BF16>(a[it], b[it]);
+        d_m[((int64_t)h * N + jm[it]) * LPR + part] = scale16<BF16>(a[it], g[it]);
+        const uintx4_t sc = scale16<BF16>(a[it], alpha);
+        d_s[((int64_t)h * N + js[it]) * LPR + part] = sc;
+        d_f[((int64_t)h * N + jf[it]) * LPR + part] = sc;
+      }
+  }
+#pragma unroll
+  for (int it = 0; it < IT; ++it) {
+    float s = acc[it];
+#pragma unroll
+    for (int o = LPR / 2; o > 0; o >>= 1) s += __shfl_xor(s, o, kWave);
+    if (part == 0) s_part[wave][it * RPW + rsub] = s;
+  }
+  __syncthreads();
+  if (threadIdx.x < kSlotsPerBlock) {
+    const int64_t t = t0 + threadIdx.x;
+    if (t < N)
+      d_gate[t] = alpha * ((s_part[0][threadIdx.x] + s_part[1][threadIdx.x]) +
+                           (s_part[2][threadIdx.x] + s_part[3][threadIdx.x]));
+  }
+}
+
 static int bits_for(int M) {
   int b = 0;
   while ((1 << b) < M) ++b;
@@ -467,5 +634,96 @@ extern "C" int moga_unpermute_bwd(const void* d_o, const void* oh, int dtype, co
   else
     unpermute_bwd_kernel<32, false><<<blocks, 256, 0, st>>>(
         (const uintx4_t*)d_o, (const uintx4_t*)oh, perm, gate, N, H, (uintx4_t*)d_oh, d_gate);
+  return launch_status();
+}
+
+// ---------------------------------------------------------------------------------------
+// static branches
+// ---------------------------------------------------------------------------------------
+extern "C" int moga_gather_rows(const void* src, int dtype, const int32_t* index, int64_t Nk, int H,
+                                int D, void* dst, void* stream) {
+  const int bad = check_rows_args(dtype, Nk, H, D);
+  if (bad) return bad;
+  if (Nk == 0) return MOGA_OK;
+  if (!src || !index || !dst || !aligned16(src) || !aligned16(dst)) return MOGA_ERR_INVALID_ARG;
+  Rows3 p{};
+  p.src[0] = src;
+  p.dst[0] = dst;
+  const int lpr = lanes_per_row(dtype, D);
+  if (lpr == 16) launch_gather<16>(p, 1, index, Nk, H, (hipStream_t)stream);
+  else launch_gather<32>(p, 1, index, Nk, H, (hipStream_t)stream);
+  return launch_status();
+}
+
+extern "C" int moga_gather_rows_bwd(const void* d_dst, int dtype, const int32_t* inv_cu,
+                                    const int32_t* inv_slots, int64_t N, int64_t Nk, int H, int D,
+                                    int accumulate, void* d_src, void* stream) {
+  const int bad = check_rows_args(dtype, N, H, D);
+  if (bad) return bad;
+  if (Nk < 0 || Nk >= ((int64_t)1 << 31)) return MOGA_ERR_INVALID_ARG;
+  if (N == 0) return MOGA_OK;
+  if (!inv_cu || !d_src || (Nk > 0 && (!d_dst || !inv_slots))) return MOGA_ERR_INVALID_ARG;
+  if (!aligned16(d_dst) || !aligned16(d_src)) return MOGA_ERR_INVALID_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  const unsigned blocks = (unsigned)((N + kSlotsPerBlock - 1) / kSlotsPerBlock);
+  const int lpr = lanes_per_row(dtype, D);
+  if (dtype == MOGA_BF16)
+    gather_rows_bwd_kernel<16, true><<<blocks, 256, 0, st>>>((const uintx4_t*)d_dst, inv_cu, inv_slots, N, Nk, H,
+                                                             accumulate, (uintx4_t*)d_src);
+  else if (lpr == 16)
+    gather_rows_bwd_kernel<16, false><<<blocks, 256, 0, st>>>((const uintx4_t*)d_dst, inv_cu, inv_slots, N, Nk, H,
+                                                              accumulate, (uintx4_t*)d_src);
+  else
+    gather_rows_bwd_kernel<32, false><<<blocks, 256, 0, st>>>((const uintx4_t*)d_dst, inv_cu, inv_slots, N, Nk, H,
+                                                              accumulate, (uintx4_t*)d_src);
+  return launch_status();
+}
+
+extern "C" int moga_merge3_fwd(const void* a_moga, const void* a_stga, const void* a_frame, int dtype,
+                               const int32_t* inv_moga, const int32_t* inv_stga, const int32_t* inv_frame,
+                               const float* gate, int64_t N, int H, int D, void* o, void* stream) {
+  const int bad = check_rows_args(dtype, N, H, D);
+  if (bad) return bad;
+  if (N == 0) return MOGA_OK;
+  if (!a_moga || !a_stga || !a_frame || !gate || !o) return MOGA_ERR_INVALID_ARG;
+  if (!(aligned16(a_moga) && aligned16(a_stga) && aligned16(a_frame) && aligned16(o))) return MOGA_ERR_INVALID_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  const unsigned blocks = (unsigned)((N + kSlotsPerBlock - 1) / kSlotsPerBlock);
+  const float alpha = 1.f / 3.f;
+  const int lpr = lanes_per_row(dtype, D);
+#define MOGA_MERGE_FWD(LPR, BF)                                                                          \
+  merge3_fwd_kernel<LPR, BF><<<blocks, 256, 0, st>>>((const uintx4_t*)a_moga, (const uintx4_t*)a_stga,   \
+                                                     (const uintx4_t*)a_frame, inv_moga, inv_stga,       \
+                                                     inv_frame, gate, alpha, N, H, (uintx4_t*)o)
+  if (dtype == MOGA_BF16) MOGA_MERGE_FWD(16, true);
+  else if (lpr == 16) MOGA_MERGE_FWD(16, false);
+  else MOGA_MERGE_FWD(32, false);
+#undef MOGA_MERGE_FWD
+  return launch_status();
+}
+
+extern "C" int moga_merge3_bwd(const void* d_o, const void* a_moga, int dtype, const int32_t* inv_moga,
+                               const int32_t* inv_stga, const int32_t* inv_frame, const float* gate,
+                               int64_t N, int H, int D, void* d_a_moga, void* d_a_stga, void* d_a_frame,
+                               float* d_gate, void* stream) {
+  const int bad = check_rows_args(dtype, N, H, D);
+  if (bad) return bad;
+  if (N == 0) return MOGA_OK;
+  if (!d_o || !a_moga || !gate || !d_a_moga || !d_a_stga || !d_a_frame || !d_gate) return MOGA_ERR_INVALID_ARG;
+  if (!(aligned16(d_o) && aligned16(a_moga) && aligned16(d_a_moga) && aligned16(d_a_stga) && aligned16(d_a_frame)))
+    return MOGA_ERR_INVALID_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  const unsigned blocks = (unsigned)((N + kSlotsPerBlock - 1) / kSlotsPerBlock);
+  const float alpha = 1.f / 3.f;
+  const int lpr = lanes_per_row(dtype, D);
+#define MOGA_MERGE_BWD(LPR, BF)                                                                          \
+  merge3_bwd_kernel<LPR, BF><<<blocks, 256, 0, st>>>((const uintx4_t*)d_o, (const uintx4_t*)a_moga,      \
+                                                     inv_moga, inv_stga, inv_frame, gate, alpha, N, H,   \
+                                                     (uintx4_t*)d_a_moga, (uintx4_t*)d_a_stga,           \
+                                                     (uintx4_t*)d_a_frame, d_gate)
+  if (dtype == MOGA_BF16) MOGA_MERGE_BWD(16, true);
+  else if (lpr == 16) MOGA_MERGE_BWD(16, false);
+  else MOGA_MERGE_BWD(32, false);
+#undef MOGA_MERGE_BWD
   return launch_status();
 }
