@@ -43,6 +43,11 @@ def parse():
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="C4b", help="C1, C1b, C2, C3, C3b, C4, C4b (default), C5")
+    ap.add_argument("--block", action="store_true",
+                    help="time the whole three-branch attention block (MoGA + spatial-temporal groups + "
+                         "per-frame groups, forward+backward) on the workload's latent grid instead of the MoGA layer")
+    ap.add_argument("--shots", type=int, default=12, help="--block: number of equal-length shots")
+    ap.add_argument("--window", default="6x13x4", help="--block: spatial window rows x cols x frames per run")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a kernel of known traffic, used to scale "
@@ -115,6 +120,55 @@ def cpu_baseline(w, budget_s=20.0):
     }
 
 
+def run_block(args):
+    """--block: one pass of the three-branch block (Section 3.2) per step, whole-call timing."""
+    import numpy as np
+    import torch
+    from paper_2510_18692_amd import binding as mg
+    from paper_2510_18692_amd import flops
+    from paper_2510_18692_amd import workloads as wl
+    mg.load()
+    w = wl.WORKLOADS[args.workload]
+    T, Hh, Ww = (int(v) for v in w.grid.split("x"))
+    wh, ww, tg = (int(v) for v in args.window.split("x"))
+    shots = np.minimum(np.arange(T) * args.shots // T, args.shots - 1)
+    torch.cuda.set_device(0)
+    inp = wl.make_inputs(w, "cuda")
+    si = mg.moga_stga_build_index(T, Hh, Ww, wh, ww, tg, shots)
+    torch.cuda.synchronize()
+
+    def step():
+        fwd = mg.visual_forward(inp["X"], inp["W"], inp["Q"], inp["K"], inp["V"], w.scale, (T, Hh, Ww), si)
+        counts = fwd["pm"]["counts"]
+        bwd = mg.visual_backward(fwd, inp["X"], inp["W"], inp["dO"], w.scale)
+        del fwd, bwd
+        return counts
+
+    for _ in range(args.warmup):
+        step()
+        torch.cuda.synchronize()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        counts = step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    counts = counts.cpu().tolist()
+    cu_q, cu_k = si["cu_q"].cpu().numpy().astype(np.int64), si["cu_k"].cpu().numpy().astype(np.int64)
+    pairs = {"moga": flops.sum_sq(counts), "stga": int(((cu_q[1:] - cu_q[:-1]) * (cu_k[1:] - cu_k[:-1])).sum()),
+             "frame": T * (Hh * Ww) ** 2}
+    total = 14.0 * w.H * w.D * sum(pairs.values())      # 4 forward + 10 backward per pair, head and channel
+    print(json.dumps({
+        "metric": "three-branch attention block effective TFLOP/s (attention FLOPs of all branches, fwd+bwd)",
+        "value": round(total / (ms * 1e-3) / 1e12, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms, 3), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"{w.name} + static branches: grid {w.grid}, {args.shots} shots, window {args.window}, "
+                               f"{si['n_groups']} spatial-temporal groups, {si['n_keys']} listed keys",
+                   "pairs": pairs, "pairs_over_N2": round(sum(pairs.values()) / float(w.N) ** 2, 5)},
+    }), flush=True)
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -129,6 +183,8 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    if args.block:
+        return run_block(args)
     mg.load()
     w = wl.WORKLOADS[args.workload]
     torch.cuda.set_device(0)

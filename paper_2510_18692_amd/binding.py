@@ -374,3 +374,52 @@ def moga_backward(fwd, x, w, d_o, softmax_scale, want_dx=False, stream=None):
                               stream=stream)
     return {"d_q": d_q, "d_k": d_k, "d_v": d_v, "d_w": d_w, "d_x": d_x, "d_gate": d_gate,
             "d_oh": d_oh, "d_qh": d_qh, "d_kh": d_kh, "d_vh": d_vh}
+
+
+def visual_forward(x, w, q, k, v, softmax_scale, grid, static_index, stream=None):
+    """The three-branch attention block of Section 3.2: MoGA (Alg. 1, gated by Eq. 5), the
+    spatial-temporal groups of `static_index` (from moga_stga_build_index) and the per-frame groups,
+    averaged by moga_merge3_fwd.  Returns a dict with everything the backward needs."""
+    T, Hh, Ww = grid
+    N = T * Hh * Ww
+    si = static_index
+    dev = q.device
+    group, gate, probs, _ = moga_route(x, w, want_probs=True, stream=stream)
+    pm = moga_permute(group, w.shape[0], q, k, v, stream=stream)
+    a_m, lse_m = moga_group_attn_fwd(pm["qh"], pm["kh"], pm["vh"], pm["cu_seqlens"], softmax_scale, stream=stream)
+    qs = moga_gather_rows(q, si["q_index"], stream=stream)
+    ks = moga_gather_rows(k, si["kv_index"], stream=stream)
+    vs = moga_gather_rows(v, si["kv_index"], stream=stream)
+    a_s, lse_s = moga_varlen_attn_fwd(qs, ks, vs, si["cu_q"], si["cu_k"], softmax_scale, stream=stream)
+    ident = torch.arange(N + 1, dtype=torch.int32, device=dev)
+    cu_f = torch.arange(T + 1, dtype=torch.int32, device=dev) * (Hh * Ww)
+    qf, kf, vf = (moga_gather_rows(t, ident[:N], stream=stream) for t in (q, k, v))
+    a_f, lse_f = moga_varlen_attn_fwd(qf, kf, vf, cu_f, cu_f, softmax_scale, stream=stream)
+    o = moga_merge3_fwd(a_m, a_s, a_f, pm["inv_perm"], si["q_slot"], None, gate, stream=stream)
+    return {"o": o, "group": group, "gate": gate, "probs": probs, "pm": pm, "a_m": a_m, "lse_m": lse_m,
+            "qs": qs, "ks": ks, "vs": vs, "a_s": a_s, "lse_s": lse_s, "qf": qf, "kf": kf, "vf": vf,
+            "a_f": a_f, "lse_f": lse_f, "cu_f": cu_f, "ident": ident, "si": si}
+
+
+def visual_backward(fwd, x, w, d_o, softmax_scale, stream=None):
+    """Backward of `visual_forward` -> dict(d_q, d_k, d_v [N, H, D], d_w [M, d_model], d_gate [N])."""
+    pm, si, ident = fwd["pm"], fwd["si"], fwd["ident"]
+    N = d_o.shape[0]
+    d_m, d_s, d_f, d_gate = moga_merge3_bwd(d_o, fwd["a_m"], pm["inv_perm"], si["q_slot"], None, fwd["gate"],
+                                            stream=stream)
+    dqm, dkm, dvm = moga_group_attn_bwd(d_m, pm["qh"], pm["kh"], pm["vh"], fwd["a_m"], fwd["lse_m"],
+                                        pm["cu_seqlens"], softmax_scale, stream=stream)
+    d_q, d_k, d_v = moga_permute_bwd(dqm, dkm, dvm, pm["perm"], stream=stream)
+    del dqm, dkm, dvm, d_m
+    dqs, dks, dvs = moga_varlen_attn_bwd(d_s, fwd["qs"], fwd["ks"], fwd["vs"], fwd["a_s"], fwd["lse_s"],
+                                         si["cu_q"], si["cu_k"], softmax_scale, stream=stream)
+    moga_gather_rows_bwd(dqs, ident, si["q_slot"], N, d_src=d_q, stream=stream)
+    moga_gather_rows_bwd(dks, si["inv_cu"], si["inv_slots"], N, d_src=d_k, stream=stream)
+    moga_gather_rows_bwd(dvs, si["inv_cu"], si["inv_slots"], N, d_src=d_v, stream=stream)
+    del dqs, dks, dvs, d_s
+    dqf, dkf, dvf = moga_varlen_attn_bwd(d_f, fwd["qf"], fwd["kf"], fwd["vf"], fwd["a_f"], fwd["lse_f"],
+                                         fwd["cu_f"], fwd["cu_f"], softmax_scale, stream=stream)
+    for dst, src in ((d_q, dqf), (d_k, dkf), (d_v, dvf)):
+        moga_gather_rows_bwd(src, ident, ident[:N], N, d_src=dst, stream=stream)
+    d_w, _ = moga_route_bwd(x, w, fwd["probs"], fwd["group"], fwd["gate"], d_gate, stream=stream)
+    return {"d_q": d_q, "d_k": d_k, "d_v": d_v, "d_w": d_w, "d_gate": d_gate}

@@ -71,42 +71,14 @@ def test_merge_of_three_branches_and_its_backward(dtype, D):
     np.testing.assert_allclose(P.to64(d_gate), ref_g, rtol=1e-4, atol=1e-3)
 
 
-def visual_block_gpu(inp, grid, wh, ww, tg, shot, scale, M):
-    """The three-branch block through the C ABI: forward and backward.  Returns dicts of GPU tensors."""
+def visual_block_gpu(inp, grid, wh, ww, tg, shot, scale):
+    """The three-branch block through the C ABI, forward and backward."""
     T, Hh, Ww = grid
-    N = T * Hh * Ww
-    X, W, Q, K, V, dO = (inp[k] for k in ("X", "W", "Q", "K", "V", "dO"))
-    H, D = Q.shape[1], Q.shape[2]
     si = mg.moga_stga_build_index(T, Hh, Ww, wh, ww, tg, shot)
-    cu_f = (torch.arange(T + 1, dtype=torch.int32) * (Hh * Ww)).cuda()
-    ident = torch.arange(N, dtype=torch.int32).cuda()
-    # dynamic branch
-    group, gate, probs, _ = mg.moga_route(X, W, want_probs=True)
-    pm = mg.moga_permute(group, M, Q, K, V)
-    a_m, lse_m = mg.moga_group_attn_fwd(pm["qh"], pm["kh"], pm["vh"], pm["cu_seqlens"], scale)
-    # spatial-temporal groups
-    qs, ks, vs = mg.moga_gather_rows(Q, si["q_index"]), mg.moga_gather_rows(K, si["kv_index"]), mg.moga_gather_rows(V, si["kv_index"])
-    a_s, lse_s = mg.moga_varlen_attn_fwd(qs, ks, vs, si["cu_q"], si["cu_k"], scale)
-    # per-frame groups
-    qf, kf, vf = (mg.moga_gather_rows(t, ident) for t in (Q, K, V))
-    a_f, lse_f = mg.moga_varlen_attn_fwd(qf, kf, vf, cu_f, cu_f, scale)
-    o = mg.moga_merge3_fwd(a_m, a_s, a_f, pm["inv_perm"], si["q_slot"], None, gate)
-    fwd = {"o": o, "group": group, "gate": gate}
-    # backward
-    d_m, d_s, d_f, d_gate = mg.moga_merge3_bwd(dO, a_m, pm["inv_perm"], si["q_slot"], None, gate)
-    dqm, dkm, dvm = mg.moga_group_attn_bwd(d_m, pm["qh"], pm["kh"], pm["vh"], a_m, lse_m, pm["cu_seqlens"], scale)
-    d_q, d_k, d_v = mg.moga_permute_bwd(dqm, dkm, dvm, pm["perm"])
-    dqs, dks, dvs = mg.moga_varlen_attn_bwd(d_s, qs, ks, vs, a_s, lse_s, si["cu_q"], si["cu_k"], scale)
-    one = torch.arange(N + 1, dtype=torch.int32).cuda()
-    mg.moga_gather_rows_bwd(dqs, one, si["q_slot"], N, d_src=d_q)
-    mg.moga_gather_rows_bwd(dks, si["inv_cu"], si["inv_slots"], N, d_src=d_k)
-    mg.moga_gather_rows_bwd(dvs, si["inv_cu"], si["inv_slots"], N, d_src=d_v)
-    dqf, dkf, dvf = mg.moga_varlen_attn_bwd(d_f, qf, kf, vf, a_f, lse_f, cu_f, cu_f, scale)
-    for dst, src in ((d_q, dqf), (d_k, dkf), (d_v, dvf)):
-        mg.moga_gather_rows_bwd(src, one, ident, N, d_src=dst)
-    d_w, _ = mg.moga_route_bwd(X, W, probs, group, gate, d_gate)
+    fwd = mg.visual_forward(inp["X"], inp["W"], inp["Q"], inp["K"], inp["V"], scale, grid, si)
+    bwd = mg.visual_backward(fwd, inp["X"], inp["W"], inp["dO"], scale)
     torch.cuda.synchronize()
-    return fwd, {"d_q": d_q, "d_k": d_k, "d_v": d_v, "d_w": d_w}
+    return fwd, bwd
 
 
 @pytest.mark.parametrize("dtype,D,H,d_model", [("f32", 64, 2, 128), ("bf16", 128, 3, 256)])
@@ -124,7 +96,7 @@ def test_three_branch_block_forward_and_backward(dtype, D, H, d_model):
     ref = sto.visual_attention(X64, W64, Q64, K64, V64, scale, (T, Hh, Ww), wh, ww, tg, shot)
     refb = sto.visual_attention_bwd(ref, X64, W64, Q64, K64, V64, dO64, scale)
     inp = {k: t.cuda() for k, t in (("X", X), ("W", W), ("Q", Q), ("K", K), ("V", V), ("dO", dO))}
-    fwd, bwd = visual_block_gpu(inp, (T, Hh, Ww), wh, ww, tg, shot, scale, M)
+    fwd, bwd = visual_block_gpu(inp, (T, Hh, Ww), wh, ww, tg, shot, scale)
     assert not P.check_assignment(fwd["group"].cpu().numpy(), ref["moga"])
     if dtype == "f32":
         say("  O", P.assert_close_f32(P.to64(fwd["o"]), ref["O"], "O"))
