@@ -43,6 +43,9 @@ def parse():
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="C4b", help="C1, C1b, C2, C3, C3b, C4, C4b (default), C5")
+    ap.add_argument("--graph", action="store_true",
+                    help="record one step into a HIP graph and time its replays (whole-step time only; for the "
+                         "small, launch-bound workloads)")
     ap.add_argument("--block", action="store_true",
                     help="time the whole three-branch attention block (MoGA + spatial-temporal groups + "
                          "per-frame groups, forward+backward) on the workload's latent grid instead of the MoGA layer")
@@ -234,6 +237,25 @@ def main():
         out = step()
         torch.cuda.synchronize()
         del out
+    graph_ms = None
+    if args.graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            held = step()
+        graph.replay()
+        torch.cuda.synchronize()
+        tg0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - tg0) * 1e3 / args.steps
+        del held, graph
     nev = len(names) + 1
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(nev)] for _ in range(args.steps)]
     torch.cuda.synchronize()
@@ -287,6 +309,8 @@ def main():
         "roofline": roof,
         "calls": calls,
     }
+    if graph_ms is not None:
+        line["graph_replay_ms_per_step"] = round(graph_ms, 4)
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(line), flush=True)
