@@ -159,6 +159,19 @@ int moga_route_bwd(const void* x, int x_dtype, const float* w, const float* prob
                    void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Alg. 1 steps 3-4 without materialising the permuted tensors: the kernel loads the rows of group g
+ * through perm (row j of the sorted order is token perm[j]) from the token-order tensors
+ * q, k, v [N, H, D], and writes o[perm[j]][h][:] = gate[perm[j]] * attention row j (Eq. 5) in
+ * token order.  perm, cu_seqlens as written by moga_permute (which may be called with NULL
+ * q, k, v so that it only builds the index); gate from moga_route.  lse [H, N] fp32 stays in
+ * sorted order.  BF16, D = 128 only.  Same result as moga_permute + moga_group_attn_fwd +
+ * moga_unpermute up to one bf16 rounding (the ungated output is never rounded).
+ */
+int moga_fused_attn_fwd(const void* q, const void* k, const void* v, int dtype, int64_t N, int H, int D,
+                        const int32_t* perm, const float* gate, const int32_t* cu_seqlens, int M,
+                        float softmax_scale, void* o, float* lse, void* stream);
+
+/*
  * Attention inside static groups whose queries and keys are listed separately (Section 3.2,
  * "Spatial-Temporal Group Attention": a group's keys and values may hold more rows than its
  * queries, e.g. latent frames added from adjacent shots).  Group g attends the query rows

@@ -38,6 +38,7 @@ _SIGNATURES = {
     "moga_permute_bwd": (_i32, [_vp, _vp, _vp, _i32, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp]),
     "moga_route_bwd": (_i32, [_vp, _i32, _vp, _vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _vp, _vp,
                               _sz, _vp]),
+    "moga_fused_attn_fwd": (_i32, [_vp, _vp, _vp, _i32, _i64, _i32, _i32, _vp, _vp, _vp, _i32, _f32, _vp, _vp, _vp]),
     "moga_varlen_attn_fwd": (_i32, [_vp, _vp, _vp, _i32, _i64, _i64, _i32, _i32, _vp, _vp, _i32, _f32, _vp, _vp,
                                     _vp, _sz, _vp]),
     "moga_varlen_attn_bwd": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _i64, _i64, _i32, _i32, _vp, _vp, _i32,
@@ -228,6 +229,18 @@ def moga_route_bwd(x, w, probs, group, gate, d_gate, want_dx=False, stream=None)
                                _p(d_w), _p(d_x), _p(ws), ws.numel(), _stream(stream))
     _check("moga_route_bwd", st)
     return d_w, d_x
+
+
+def moga_fused_attn_fwd(q, k, v, perm, gate, cu_seqlens, softmax_scale, stream=None):
+    """q, k, v [N, H, D] token order -> (o [N, H, D] gated, token order; lse f32 [H, N] sorted order)"""
+    N, H, D = q.shape
+    M = cu_seqlens.shape[0] - 1
+    o = torch.empty_like(q)
+    lse = torch.empty((H, N), dtype=torch.float32, device=q.device)
+    st = load().moga_fused_attn_fwd(_p(q), _p(k), _p(v), _dt(q), N, H, D, _p(perm), _p(gate), _p(cu_seqlens), M,
+                                    float(softmax_scale), _p(o), _p(lse), _stream(stream))
+    _check("moga_fused_attn_fwd", st)
+    return o, lse
 
 
 def moga_varlen_attn_fwd(qh, kh, vh, cu_seqlens_q, cu_seqlens_k, softmax_scale, stream=None):

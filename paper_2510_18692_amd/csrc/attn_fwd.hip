@@ -172,6 +172,25 @@ extern "C" int moga_group_attn_fwd(const void* qh, const void* kh, const void* v
                          softmax_scale, oh, lse, (hipStream_t)stream);
 }
 
+extern "C" int moga_fused_attn_fwd(const void* q, const void* k, const void* v, int dtype, int64_t N,
+                                   int H, int D, const int32_t* perm, const float* gate,
+                                   const int32_t* cu_seqlens, int M, float softmax_scale, void* o,
+                                   float* lse, void* stream) {
+  const int bad = check_attn_args(N, N, H, D, M, softmax_scale, dtype);
+  if (bad) return bad;
+  if (M > MOGA_MAX_GROUPS || dtype != MOGA_BF16) return MOGA_ERR_UNSUPPORTED;
+  if (N == 0) return MOGA_OK;
+  if (!q || !k || !v || !perm || !gate || !cu_seqlens || !o || !lse) return MOGA_ERR_INVALID_ARG;
+  if (!(aligned16(q) && aligned16(k) && aligned16(v) && aligned16(o))) return MOGA_ERR_INVALID_ARG;
+  const int64_t tiles = max_tiles(N, M, 256);
+  const int64_t blocks = (tiles * H + 7) / 8 * 8;
+  if (blocks >= ((int64_t)1 << 31)) return MOGA_ERR_UNSUPPORTED;
+  attn_fwd_bf16_pipe_kernel<8, 1, true><<<(unsigned)blocks, 512, 0, (hipStream_t)stream>>>(
+      (const unsigned short*)q, (const unsigned short*)k, (const unsigned short*)v, cu_seqlens, cu_seqlens,
+      nullptr, M, N, N, H, softmax_scale, (int)tiles, (unsigned short*)o, lse, perm, gate);
+  return launch_status();
+}
+
 extern "C" size_t moga_varlen_attn_fwd_ws_bytes(int G) { return ((size_t)G + 1) * sizeof(int32_t); }
 
 extern "C" int moga_varlen_attn_fwd(const void* qh, const void* kh, const void* vh, int dtype,

@@ -146,6 +146,14 @@ struct PipeDma {
   int row0;                // this lane's row inside a tile for round 0 (round i is + 4*NW*i)
   unsigned chunk_off;      // swizzled 16-byte chunk inside the row, in bytes
   int last_row;            // last valid row, relative to the group's first row
+  // gather mode: rows are fetched through an index list from token-major tensors; kbase / vbase
+  // then point at token 0 of this head
+  const int32_t* rows;     // index list at the group's first row (wave-uniform)
+  int64_t tok_stride;      // bytes between two tokens
+  int wave_row;            // 4 * wave (wave-uniform)
+  // tokens of the rows this wave moves in the next tile to be issued, rounds 0 and 1 (wave-uniform;
+  // separate scalars so that they stay in scalar registers)
+  int ta0, ta1, ta2, ta3, tb0, tb1, tb2, tb3;
 };
 
 // Issue the loads of the 64-key tile starting at group-relative row kv0 into ring slot `buf`:
@@ -162,17 +170,74 @@ __device__ __forceinline__ void pipe_issue_tile(const PipeDma& d, int kv0, int b
   }
 }
 
+// Gather mode: the tokens of the tile's rows were read (as scalars) while the previous tile was
+// issued; select this lane's token, form the two 64-bit addresses, issue, then read the tokens of
+// the following tile.
+// Scalar (constant-address-space) read of one index: address and result are wave-uniform.
+__device__ __forceinline__ int scalar_load_index(const int32_t* p, int i) {
+  typedef const int32_t __attribute__((address_space(4))) * cptr;
+  return __builtin_amdgcn_readfirstlane(((cptr)(uintptr_t)p)[i]);
+}
+
+template <int NW>
+__device__ __forceinline__ void pipe_load_tokens(PipeDma& d, int kv0) {
+  const int r0 = kv0 + d.wave_row;
+  d.ta0 = scalar_load_index(d.rows, min(r0 + 0, d.last_row));
+  d.ta1 = scalar_load_index(d.rows, min(r0 + 1, d.last_row));
+  d.ta2 = scalar_load_index(d.rows, min(r0 + 2, d.last_row));
+  d.ta3 = scalar_load_index(d.rows, min(r0 + 3, d.last_row));
+  if (NW == 8) {
+    d.tb0 = scalar_load_index(d.rows, min(r0 + 32, d.last_row));
+    d.tb1 = scalar_load_index(d.rows, min(r0 + 33, d.last_row));
+    d.tb2 = scalar_load_index(d.rows, min(r0 + 34, d.last_row));
+    d.tb3 = scalar_load_index(d.rows, min(r0 + 35, d.last_row));
+  }
+}
+
+__device__ __forceinline__ int select4(int sub, int a, int b, int c, int e) {
+  int t = a;
+  t = sub == 1 ? b : t;
+  t = sub == 2 ? c : t;
+  t = sub == 3 ? e : t;
+  return t;
+}
+
+template <int NW>
+__device__ __forceinline__ void pipe_issue_tile_gather(PipeDma& d, int kv0, int buf) {
+  static_assert(NW == 8, "gather mode moves two rounds of four rows per wave");
+  const unsigned boff = (unsigned)buf * kPipeTileBytes;
+  const int sub = d.row0 & 3;
+  const int64_t off_a = (int64_t)select4(sub, d.ta0, d.ta1, d.ta2, d.ta3) * d.tok_stride + d.chunk_off;
+  const int64_t off_b = (int64_t)select4(sub, d.tb0, d.tb1, d.tb2, d.tb3) * d.tok_stride + d.chunk_off;
+  lds_dma16((const char*)d.kbase + off_a, d.lds_k + boff);
+  lds_dma16((const char*)d.vbase + off_a, d.lds_v + boff);
+  lds_dma16((const char*)d.kbase + off_b, d.lds_k + boff + 4 * NW * 256);
+  lds_dma16((const char*)d.vbase + off_b, d.lds_v + boff + 4 * NW * 256);
+  pipe_load_tokens<NW>(d, kv0 + 64);
+}
+
+template <int NW, bool GATHER>
+__device__ __forceinline__ void pipe_issue(PipeDma& d, int kv0, int buf) {
+  if (GATHER) pipe_issue_tile_gather<NW>(d, kv0, buf);
+  else pipe_issue_tile<NW>(d, kv0, buf);
+}
+
 // Queries are the rows cu_q[g] .. cu_q[g+1] of qh [H, Nq, 128]; their keys and values the rows
 // cu_k[g] .. cu_k[g+1] of kh, vh [H, Nk, 128] (cu_k == cu_q and Nk == Nq for MoGA's groups).
 // tile_start: NULL (tile lookup from cu_q inside the block, M <= MOGA_MAX_GROUPS) or the
 // pre-summed first-tile index of every group.
-template <int NW, int QW>
+//
+// GATHER: qh, kh, vh and oh are token-major [N, H, 128]; row j of a group is token perm[j] (the
+// permutation of Alg. 1 is applied while loading, nothing is materialised) and the output row is
+// multiplied by gate[token] (Eq. 5) and written to its token.  lse stays in sorted order [H, N].
+template <int NW, int QW, bool GATHER = false>
 __global__ __launch_bounds__(NW * 64) void attn_fwd_bf16_pipe_kernel(
     const unsigned short* __restrict__ qh, const unsigned short* __restrict__ kh,
     const unsigned short* __restrict__ vh, const int32_t* __restrict__ cu_q,
     const int32_t* __restrict__ cu_k, const int32_t* __restrict__ tile_start, int M,
     int64_t Nq, int64_t Nk, int H, float scale, int tiles_per_head, unsigned short* __restrict__ oh,
-    float* __restrict__ lse) {
+    float* __restrict__ lse, const int32_t* __restrict__ perm = nullptr,
+    const float* __restrict__ gate = nullptr) {
   constexpr int BM = NW * 32 * QW;
   constexpr int kDmaPerTile = 2 * (16 / NW);   // direct-to-LDS instructions per thread per tile
   static_assert(NW == 4 || NW == 8, "4 or 8 waves");
@@ -208,7 +273,8 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_bf16_pipe_kernel(
     for (int qw = 0; qw < QW; ++qw) {
       const int qrow = q0 + (wave * QW + qw) * 32 + r;
       if (qrow < ge) {
-        uintx4_t* op = (uintx4_t*)(oh + (head_off + qrow) * kHeadDim + 64 * h);
+        const int64_t orow = GATHER ? (int64_t)perm[qrow] * H + head : head_off + qrow;
+        uintx4_t* op = (uintx4_t*)(oh + orow * kHeadDim + 64 * h);
         const uintx4_t z = {0u, 0u, 0u, 0u};
 #pragma unroll
         for (int i = 0; i < 8; ++i) op[i] = z;
@@ -224,22 +290,29 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_bf16_pipe_kernel(
   for (int qw = 0; qw < QW; ++qw) {
     int qrow = q0 + (wave * QW + qw) * 32 + r;
     if (qrow > ge - 1) qrow = ge - 1;
-    const unsigned short* qp = qh + (head_off + qrow) * kHeadDim + 8 * h;
+    const int64_t irow = GATHER ? (int64_t)perm[qrow] * H + head : head_off + qrow;
+    const unsigned short* qp = qh + irow * kHeadDim + 8 * h;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) qf[qw][ks] = *(const bf16x8_t*)(qp + 16 * ks);
   }
 
   // ---- direct-to-LDS loads: first kPipeAhead + 1 tiles (always issued; rows are clamped)
   PipeDma dma;
-  dma.kbase = uniform_ptr(kh + (head_off_k + gs) * kHeadDim);
-  dma.vbase = uniform_ptr(vh + (head_off_k + gs) * kHeadDim);
+  dma.kbase = uniform_ptr(GATHER ? kh + (int64_t)head * kHeadDim : kh + (head_off_k + gs) * kHeadDim);
+  dma.vbase = uniform_ptr(GATHER ? vh + (int64_t)head * kHeadDim : vh + (head_off_k + gs) * kHeadDim);
   dma.lds_k = lds_addr_uniform(&Ks[0][0]) + wave * 1024;
   dma.lds_v = lds_addr_uniform(&Vs[0][0]) + wave * 1024;
   dma.row0 = 4 * wave + (lane >> 4);
   dma.chunk_off = (unsigned)(((lane & 15) ^ lds_swizzle(dma.row0)) * 16);
   dma.last_row = n - 1;
+  if (GATHER) {
+    dma.rows = (const int32_t*)uniform_ptr(perm + gs);
+    dma.tok_stride = (int64_t)H * kHeadDim * 2;
+    dma.wave_row = 4 * wave;
+    pipe_load_tokens<NW>(dma, 0);
+  }
 #pragma unroll
-  for (int t = 0; t <= kPipeAhead; ++t) pipe_issue_tile<NW>(dma, 64 * t, t);
+  for (int t = 0; t <= kPipeAhead; ++t) pipe_issue<NW, GATHER>(dma, 64 * t, t);
 
   // ---- per-lane LDS read addresses
   PipeLane ln;
@@ -307,7 +380,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_bf16_pipe_kernel(
   pipe_step<QW, true, (B) * kPipeTileBytes + 8192, (B) * kPipeTileBytes>(ln, 0, 0, qf, st, s_a, s_b, mx, c); \
   __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * (kPipeAhead - 1)));                       \
   __syncthreads();                                                                              \
-  pipe_issue_tile<NW>(dma, 32 * s + 64 * ((B) + 1 + kPipeAhead), ((B) + 1 + kPipeAhead) & 3); \
+  pipe_issue<NW, GATHER>(dma, 32 * s + 64 * ((B) + 1 + kPipeAhead), ((B) + 1 + kPipeAhead) & 3); \
   maybe_rescale<QW>(st, mx, c, tau);                                                            \
   pipe_step<QW, true, (((B) + 1) & 3) * kPipeTileBytes, (B) * kPipeTileBytes + 8192>(ln, 0, 0, qf, st, s_b, s_a, mx, c);
   for (; s + 8 <= nfull - 1; s += 8) {   // steps s .. s+7 and their successors are full
@@ -325,7 +398,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_bf16_pipe_kernel(
     pipe_step<QW, true>(ln, slot + 8192, slot, qf, st, s_a, s_b, mx, c);
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * (kPipeAhead - 1)));
     __syncthreads();
-    pipe_issue_tile<NW>(dma, 32 * (s + 2) + 64 * kPipeAhead, ((s >> 1) + 1 + kPipeAhead) & 3);
+    pipe_issue<NW, GATHER>(dma, 32 * (s + 2) + 64 * kPipeAhead, ((s >> 1) + 1 + kPipeAhead) & 3);
     maybe_rescale<QW>(st, mx, c, tau);
     pipe_step<QW, true>(ln, slot_next, slot + 8192, qf, st, s_b, s_a, mx, c);
     s += 2;
@@ -338,7 +411,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_bf16_pipe_kernel(
     if (half == 1 && has_next) {   // the next step starts a new tile
       __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * (kPipeAhead - 1)));
       __syncthreads();
-      pipe_issue_tile<NW>(dma, 32 * (s + 1) + 64 * kPipeAhead, (buf + 1 + kPipeAhead) & 3);
+      pipe_issue<NW, GATHER>(dma, 32 * (s + 1) + 64 * kPipeAhead, (buf + 1 + kPipeAhead) & 3);
     }
     maybe_rescale<QW>(st, mx, c, tau);
     const unsigned voff = buf * kPipeTileBytes + half * 8192;
@@ -362,10 +435,16 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_bf16_pipe_kernel(
   for (int qw = 0; qw < QW; ++qw) {
     const auto rr = __builtin_amdgcn_permlane32_swap(__float_as_uint(st.l[qw]), __float_as_uint(st.l[qw]), false, false);
     const float lt = __uint_as_float(rr[0]) + __uint_as_float(rr[1]);
-    const float inv = 1.f / lt;
+    float inv = 1.f / lt;
     const int qrow = q0 + (wave * QW + qw) * 32 + r;
     if (qrow < ge) {
-      unsigned short* op = oh + (head_off + qrow) * kHeadDim + 4 * h;
+      int64_t orow = head_off + qrow;
+      if (GATHER) {
+        const int tok = perm[qrow];
+        orow = (int64_t)tok * H + head;
+        inv *= gate[tok];
+      }
+      unsigned short* op = oh + orow * kHeadDim + 4 * h;
 #pragma unroll
       for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
