@@ -50,7 +50,9 @@ def parse():
                     help="time the whole three-branch attention block (MoGA + spatial-temporal groups + "
                          "per-frame groups, forward+backward) on the workload's latent grid instead of the MoGA layer")
     ap.add_argument("--shots", type=int, default=12, help="--block: number of equal-length shots")
-    ap.add_argument("--window", default="6x13x4", help="--block: spatial window rows x cols x frames per run")
+    ap.add_argument("--window", default="8x13x0",
+                    help="--block: spatial window rows x cols x frames per run (0 = a whole shot). The default is the "
+                         "4 x 4 partition of the 30 x 52 latent frame that the paper pairs with long contexts")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a kernel of known traffic, used to scale "
@@ -134,6 +136,7 @@ def run_block(args):
     w = wl.WORKLOADS[args.workload]
     T, Hh, Ww = (int(v) for v in w.grid.split("x"))
     wh, ww, tg = (int(v) for v in args.window.split("x"))
+    tg = tg if tg > 0 else T
     shots = np.minimum(np.arange(T) * args.shots // T, args.shots - 1)
     torch.cuda.set_device(0)
     inp = wl.make_inputs(w, "cuda")
