@@ -213,10 +213,17 @@ static int launch_attn_bwd(const void* d_oh, const void* qh, const void* kh, con
       const int64_t blocks = (tiles * H + 7) / 8 * 8;
       if (blocks >= ((int64_t)1 << 31)) return MOGA_ERR_UNSUPPORTED;
       if (ts_k) tile_start_kernel<<<1, 1024, 0, st>>>(cu_k, M, 128, ts_k);
+#ifdef MOGA_DKDV_ONE_WAVE
       attn_bwd_dkdv_pipe_kernel<4><<<(unsigned)blocks, 256, 0, st>>>(
           (const unsigned short*)d_oh, (const unsigned short*)qh, (const unsigned short*)kh,
           (const unsigned short*)vh, lse2, delta, cu_q, cu_k, ts_k, M, Nq, Nk, H, softmax_scale,
           (int)tiles, (unsigned short*)d_kh, (unsigned short*)d_vh);
+#else
+      attn_bwd_dkdv_ab_kernel<<<(unsigned)blocks, 512, 0, st>>>(
+          (const unsigned short*)d_oh, (const unsigned short*)qh, (const unsigned short*)kh,
+          (const unsigned short*)vh, lse2, delta, cu_q, cu_k, ts_k, M, Nq, Nk, H, softmax_scale,
+          (int)tiles, (unsigned short*)d_kh, (unsigned short*)d_vh);
+#endif
     }
     {
       const int64_t tiles = max_tiles(Nq, M, 256);

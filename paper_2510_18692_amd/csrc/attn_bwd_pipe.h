@@ -570,4 +570,289 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_pipe_kernel(
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// dK, dV with two waves per SIMD: the four products are split between two waves that own the
+// same 32 key rows.  Wave A (waves 0-3) holds K and the dV^T accumulators: it computes S = Q K^T,
+// P = exp2(c*S - lse*log2e), hands P to its partner through LDS and accumulates dV^T += dO^T P.
+// Wave B (waves 4-7, same SIMD as its partner) holds V and the dK^T accumulators: it computes
+// dP = dO V^T - delta, waits for P, forms dS = P * dP and accumulates dK^T += Q^T dS.  Each wave
+// needs 64 accumulator registers instead of 128, so two waves fit on a SIMD and fill each other's
+// waits.  One block-wide barrier per 64-query tile (tile landed, ring slot free); P is handed over
+// inside the pair with a flag in LDS (release store by A, acquire spin by B), so the pairs and the
+// two roles drift apart instead of meeting twice per tile.  A never waits for B outside the block
+// barrier, so every spin ends.
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ void lds_write_b128(unsigned addr, bf16x8_t v) {
+  *(bf16x8_t __attribute__((address_space(3)))*)(uintptr_t)addr = v;
+}
+
+struct AbLane {
+  unsigned nat[8];      // rows of Q (A) or dO (B): A operand of the score product, slot 0, half 0
+  unsigned tr[4][2];    // transposed reads of dO (A) or Q (B) for d tile dt, rows +0 / +4
+  unsigned init_addr;   // -lse/scale (A) or -delta (B) of the lane's first row
+  unsigned p_addr;      // this lane's 16 bytes in the pair's P buffer (unit 0, kstep 0)
+};
+
+// scores of one 32-query unit: acc starts from the per-row constants, then 8 chained MFMAs
+template <int SOFF, int SROW>
+__device__ __forceinline__ void ab_scores(const AbLane& ln, unsigned off, unsigned off_row,
+                                          const bf16x8_t (&kvf)[8], floatx16_t& acc) {
+  bf16x8_t nat[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) nat[ks] = lds_read_b128(ln.nat[ks] + off + SOFF);
+#pragma unroll
+  for (int kstep = 0; kstep < 2; ++kstep)
+#pragma unroll
+    for (int half4 = 0; half4 < 2; ++half4) {
+      const floatx4_t iv = lds_read_f32x4(ln.init_addr + off_row + SROW + (16 * kstep + 4 * half4) * 4);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc[8 * kstep + 4 * half4 + e] = iv[e];
+    }
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(nat[ks], kvf[ks], acc, 0, 0, 0);
+}
+
+template <int SOFF>
+__device__ __forceinline__ void ab_load_tr(const AbLane& ln, unsigned off, bf16x8_t (&tr)[2][4]) {
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int kstep = 0; kstep < 2; ++kstep)
+      tr[kstep][dt] = concat_tr(lds_read_tr16_addr(ln.tr[dt][0] + off + SOFF + kstep * 16 * 256),
+                                lds_read_tr16_addr(ln.tr[dt][1] + off + SOFF + kstep * 16 * 256));
+}
+
+__device__ __forceinline__ void ab_accumulate(const bf16x8_t (&tr)[2][4], const bf16x8_t (&bop)[2],
+                                              floatx16_t (&acc)[4]) {
+#pragma unroll
+  for (int kstep = 0; kstep < 2; ++kstep)
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+      acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr[kstep][dt], bop[kstep], acc[dt], 0, 0, 0);
+}
+
+// A: P of one 32-query unit from its scores, also written to LDS for the partner.
+template <bool MASK>
+__device__ __forceinline__ void ab_make_p(const AbLane& ln, const floatx16_t& sc, float c, int h, int left, int u,
+                                          bf16x8_t (&pf)[2]) {
+#pragma unroll
+  for (int kstep = 0; kstep < 2; ++kstep) {
+    unsigned int pp[4];
+#pragma unroll
+    for (int j = 0; j < 8; j += 2) {
+      const int v = 8 * kstep + j;
+      float pa = fast_exp2(sc[v] * c), pb = fast_exp2(sc[v + 1] * c);
+      if (MASK) {
+        const int idx = 32 * u + 16 * kstep + 8 * h + j;
+        if (idx >= left) pa = 0.f;
+        if (idx + 1 >= left) pb = 0.f;
+      }
+      pp[j >> 1] = pack_bf16x2(pa, pb);
+    }
+    const uintx4_t pu = {pp[0], pp[1], pp[2], pp[3]};
+    pf[kstep] = __builtin_bit_cast(bf16x8_t, pu);
+    lds_write_b128(ln.p_addr + u * 2048 + kstep * 1024, pf[kstep]);
+  }
+}
+
+// B: dS = P * dP of one unit, P read from LDS.
+__device__ __forceinline__ void ab_take_p(const AbLane& ln, const floatx16_t& dp, int u, bf16x8_t (&dsf)[2]) {
+#pragma unroll
+  for (int kstep = 0; kstep < 2; ++kstep) {
+    const uintx4_t pu = __builtin_bit_cast(uintx4_t, lds_read_b128(ln.p_addr + u * 2048 + kstep * 1024));
+    unsigned int dd[4];
+#pragma unroll
+    for (int j = 0; j < 8; j += 2) {
+      const int v = 8 * kstep + j;
+      dd[j >> 1] = pack_bf16x2(bf16_lo_to_f32(pu[j >> 1]) * dp[v], bf16_hi_to_f32(pu[j >> 1]) * dp[v + 1]);
+    }
+    const uintx4_t du = {dd[0], dd[1], dd[2], dd[3]};
+    dsf[kstep] = __builtin_bit_cast(bf16x8_t, du);
+  }
+}
+
+// One 64-query tile for either role (role is wave-uniform; the common parts are written once so that
+// the two roles share one instruction stream, with one short role-specific piece in the middle):
+//   A: S(u0), S(u1) | P -> LDS, stamp          | dV(u0), dV(u1)
+//   B: dP(u0), dP(u1) | wait for the stamp, dS = P * dP | dK(u0), dK(u1)
+// `left`: valid query rows of the tile (MASK only).  The stamp of tile t is t + 1.
+template <bool MASK, int SOFF, int SROW>
+__device__ __forceinline__ void ab_tile(const AbLane& ln, int role, unsigned off, unsigned off_row,
+                                        const bf16x8_t (&kvf)[8], floatx16_t (&acc)[4], float c, int h, int left,
+                                        int* flag, int tile_no) {
+  floatx16_t sc[2];   // S (A) or dP (B) of the two 32-query units
+  bf16x8_t bop[2][2]; // B operand of the second product: P (A) or dS (B), per unit and 16-query step
+  bf16x8_t tr0[2][4], tr1[2][4];
+  ab_scores<SOFF, SROW>(ln, off, off_row, kvf, sc[0]);
+  ab_scores<SOFF + 8192, SROW + 128>(ln, off, off_row, kvf, sc[1]);
+  ab_load_tr<SOFF>(ln, off, tr0);   // in flight while P is computed (A) or awaited (B)
+  __builtin_amdgcn_sched_barrier(0);
+  if (role == 0) {
+    ab_make_p<MASK>(ln, sc[0], c, h, left, 0, bop[0]);
+    ab_make_p<MASK>(ln, sc[1], c, h, left, 1, bop[1]);
+    __hip_atomic_store(flag, tile_no, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);   // P of this tile is in LDS
+  } else {
+    while (__hip_atomic_load(flag, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < tile_no) __builtin_amdgcn_s_sleep(1);
+    ab_take_p(ln, sc[0], 0, bop[0]);
+    ab_take_p(ln, sc[1], 1, bop[1]);
+  }
+  ab_load_tr<SOFF + 8192>(ln, off, tr1);   // in flight while the first unit is accumulated
+  ab_accumulate(tr0, bop[0], acc);
+  ab_accumulate(tr1, bop[1], acc);
+}
+
+__global__ __launch_bounds__(512) void attn_bwd_dkdv_ab_kernel(
+    const unsigned short* __restrict__ d_oh, const unsigned short* __restrict__ qh,
+    const unsigned short* __restrict__ kh, const unsigned short* __restrict__ vh,
+    const float* __restrict__ neg_lse_over_scale, const float* __restrict__ neg_delta,
+    const int32_t* __restrict__ cu_q, const int32_t* __restrict__ cu_k,
+    const int32_t* __restrict__ tile_start, int M, int64_t Nq, int64_t Nk, int H, float scale,
+    int tiles_per_head, unsigned short* __restrict__ d_kh, unsigned short* __restrict__ d_vh) {
+  constexpr int NW = 8;
+  constexpr int BK = 128;                          // 4 pairs of waves x 32 keys
+  constexpr int kDmaPerTile = 2 * (16 / NW) + 2;
+  __shared__ __attribute__((aligned(1024))) unsigned short Qs[kPipeNBuf][64 * kHeadDim];
+  __shared__ __attribute__((aligned(1024))) unsigned short dOs[kPipeNBuf][64 * kHeadDim];
+  __shared__ __attribute__((aligned(1024))) unsigned char Ps[4][4096];   // P of one tile, per pair
+  __shared__ __attribute__((aligned(256))) float Ls[kPipeNBuf][64];      // -lse / scale
+  __shared__ __attribute__((aligned(256))) float Ds[kPipeNBuf][64];      // -delta
+  __shared__ int s_flag[4];   // per pair: number of tiles whose P has been written
+  __shared__ int s_start[MOGA_MAX_GROUPS + 1];
+  __shared__ int s_found;
+
+  const int64_t total = (int64_t)H * tiles_per_head;
+  const int64_t work = xcd_work_index(blockIdx.x, total);
+  if (work >= total) return;
+  const int head = (int)(work / tiles_per_head);
+  const int tile = (int)(work - (int64_t)head * tiles_per_head);
+  if (threadIdx.x < 4) s_flag[threadIdx.x] = 0;   // ordered before its first use by the barriers below
+  TileInfo ti;   // tiles run over the key rows of the groups
+  if (tile_start) {
+    if (!find_tile_presummed(tile_start, cu_k, M, BK, tile, ti)) return;
+  } else if (!find_tile(cu_k, M, BK, tile, s_start, &s_found, ti)) {
+    return;
+  }
+  const int ge = ti.row_end, k0 = ti.tile_row;
+  const int gs = cu_q[ti.group];
+  const int n = cu_q[ti.group + 1] - gs;
+
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int role = wave >> 2, pair = wave & 3;
+  int* flag = &s_flag[pair];
+  const int r = lane & 31, h = lane >> 5;
+  const int64_t head_off = (int64_t)head * Nk;
+  const int64_t head_off_q = (int64_t)head * Nq;
+  const float c = scale * 1.4426950408889634f;
+  const int krow = k0 + pair * 32 + r;
+  unsigned short* outp = role == 0 ? d_vh : d_kh;
+
+  if (n <= 0) {   // keys without queries: zero gradient (block-uniform branch)
+    if (krow < ge) {
+      uintx4_t* o4 = (uintx4_t*)(outp + (head_off + krow) * kHeadDim + 64 * h);
+      const uintx4_t z = {0u, 0u, 0u, 0u};
+#pragma unroll
+      for (int i = 0; i < 8; ++i) o4[i] = z;
+    }
+    return;
+  }
+
+  // K (A) or V (B) fragments of the pair's 32 key rows: B operand, lane (r, h) holds row r, d = 16*ks + 8*h + 0..7
+  const int krow_c = krow < ge ? krow : ge - 1;
+  bf16x8_t kvf[8];
+  {
+    const unsigned short* kp = (role == 0 ? kh : vh) + (head_off + krow_c) * kHeadDim + 8 * h;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) kvf[ks] = *(const bf16x8_t*)(kp + 16 * ks);
+  }
+
+  PipeDma dma;   // "k" = Q rows, "v" = dO rows of this head's group
+  dma.kbase = uniform_ptr(qh + (head_off_q + gs) * kHeadDim);
+  dma.vbase = uniform_ptr(d_oh + (head_off_q + gs) * kHeadDim);
+  dma.lds_k = lds_addr_uniform(&Qs[0][0]) + wave * 1024;
+  dma.lds_v = lds_addr_uniform(&dOs[0][0]) + wave * 1024;
+  dma.row0 = 4 * wave + (lane >> 4);
+  dma.chunk_off = (unsigned)(((lane & 15) ^ lds_swizzle(dma.row0)) * 16);
+  dma.last_row = n - 1;
+  const void* lbase = uniform_ptr(neg_lse_over_scale + head_off_q + gs);
+  const void* dbase = uniform_ptr(neg_delta + head_off_q + gs);
+  const unsigned lds_l = lds_addr_uniform(&Ls[0][0]), lds_d = lds_addr_uniform(&Ds[0][0]);
+  auto issue_tile = [&](int T) {   // every wave issues the (identical) row-constant loads so that all count alike
+    const int slot = T & 3;
+    pipe_issue_tile<NW>(dma, 64 * T, slot);
+    const unsigned roff = (unsigned)min(64 * T + lane, n - 1) * 4u;
+    lds_dma4_soff(lbase, roff, lds_l + slot * 256);
+    lds_dma4_soff(dbase, roff, lds_d + slot * 256);
+  };
+#pragma unroll
+  for (int t = 0; t <= kPipeAhead; ++t) issue_tile(t);
+
+  AbLane ln;
+  {
+    const int row_a = swap_bits_2_3(r);
+    const int sw = lds_swizzle(row_a);
+    const unsigned nb = role == 0 ? (unsigned)(uintptr_t)&Qs[0][0] : (unsigned)(uintptr_t)&dOs[0][0];
+    const unsigned tb = role == 0 ? (unsigned)(uintptr_t)&dOs[0][0] : (unsigned)(uintptr_t)&Qs[0][0];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) ln.nat[ks] = nb + row_a * 256 + (((2 * ks + h) ^ sw) << 4);
+    const int tr_r = 8 * h + ((lane & 15) >> 2);
+    const int tr_c = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
+    const int tr_e = 4 * (lane & 1);
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) {
+      ln.tr[dt][0] = tb + tr_e * 2 + tr_r * 256 + (((4 * dt + tr_c) ^ lds_swizzle(tr_r)) << 4);
+      ln.tr[dt][1] = tb + tr_e * 2 + (tr_r + 4) * 256 + (((4 * dt + tr_c) ^ lds_swizzle(tr_r + 4)) << 4);
+    }
+    ln.init_addr = (role == 0 ? (unsigned)(uintptr_t)&Ls[0][0] : (unsigned)(uintptr_t)&Ds[0][0]) + 8 * h * 4;
+    ln.p_addr = (unsigned)(uintptr_t)&Ps[0][0] + pair * 4096 + lane * 16;
+  }
+
+  floatx16_t acc[4];   // dV^T (A) or dK^T (B): 128 x 32
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[dt][v] = 0.f;
+
+  const int nfull = n >> 6;   // tiles whose 64 queries are all inside the group
+  int T = 0;
+#define MOGA_AB_TILE(B)                                                          \
+  __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * kPipeAhead));              \
+  __syncthreads();                                                               \
+  issue_tile(T + (B) + 1 + kPipeAhead);                                          \
+  ab_tile<false, (B) * kPipeTileBytes, (B) * 256>(ln, role, 0, 0, kvf, acc, c, h, 64, flag, T + (B) + 1);
+  for (; T + 4 <= nfull; T += 4) {   // four tiles per iteration: every LDS offset is an immediate
+    MOGA_AB_TILE(0)
+    MOGA_AB_TILE(1)
+    MOGA_AB_TILE(2)
+    MOGA_AB_TILE(3)
+  }
+#undef MOGA_AB_TILE
+  for (; T < nfull; ++T) {
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * kPipeAhead));
+    __syncthreads();
+    issue_tile(T + 1 + kPipeAhead);
+    ab_tile<false, 0, 0>(ln, role, ((unsigned)T & 3u) * kPipeTileBytes, ((unsigned)T & 3u) * 256, kvf, acc, c, h, 64,
+                         flag, T + 1);
+  }
+  if (n & 63) {   // last, partial tile: masked queries get P = 0 and contribute nothing
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * kPipeAhead));
+    __syncthreads();
+    ab_tile<true, 0, 0>(ln, role, ((unsigned)T & 3u) * kPipeTileBytes, ((unsigned)T & 3u) * 256, kvf, acc, c, h,
+                        n - 64 * T, flag, T + 1);
+  }
+
+  __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // drain the look-ahead loads before the LDS is released
+  if (krow < ge) {
+    const float f = role == 0 ? 1.f : scale;
+    unsigned short* op = outp + (head_off + krow) * kHeadDim + 4 * h;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        uintx2_t pk = {pack_bf16x2(acc[dt][4 * b] * f, acc[dt][4 * b + 1] * f),
+                       pack_bf16x2(acc[dt][4 * b + 2] * f, acc[dt][4 * b + 3] * f)};
+        *(uintx2_t*)(op + 32 * dt + 8 * b) = pk;
+      }
+  }
+}
+
 }  // namespace moga
