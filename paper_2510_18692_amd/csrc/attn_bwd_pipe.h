@@ -3,11 +3,14 @@
 //   attn_bwd_dq_pipe_kernel   : a wave owns 32*QW query rows (Q, dO fragments, lse, delta and
 //                               the dQ^T accumulators in registers) and sweeps 64-key tiles of
 //                               K and V; three MFMA products per tile (S^T, dP^T, dQ^T).
-//   attn_bwd_dkdv_pipe_kernel : a wave owns 32 key rows (K, V fragments, dK^T and dV^T
-//                               accumulators in registers) and sweeps 64-query tiles of Q, dO,
-//                               lse and delta; four MFMA products per tile (S, dP, dV^T, dK^T).
+//   attn_bwd_dkdv_ab_kernel   : a pair of waves on one SIMD owns 32 key rows and sweeps 64-query
+//                               tiles of Q, dO, lse and delta; one wave computes S, P and dV^T,
+//                               the other dP, dS and dK^T (P handed over through LDS).  The one
+//                               the library launches.
+//   attn_bwd_dkdv_pipe_kernel : its predecessor: all four products (S, dP, dV^T, dK^T) in one
+//                               wave, one wave per SIMD (the accumulators need > 256 registers).
 // Tiles are streamed global -> LDS by direct-to-LDS loads into a ring of four slots, two tiles
-// ahead; one block-wide barrier per tile; one wave per SIMD (the accumulators need > 256 registers).
+// ahead; one block-wide barrier per tile.
 #pragma once
 
 #include "attn_pipe.h"
