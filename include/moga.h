@@ -20,8 +20,8 @@
  *   - Notation: N tokens (batch 1), d_model router input width, M groups, H heads,
  *     D head_dim.  Token-order tensors are [N, H, D] row-major; group-contiguous
  *     ("hat") tensors are head-major [H, N, D], row j of a head being sorted slot j.
- *   - Supported: M in [1, 256]; N < 2^31; dtype F32 with D in {64, 128} (backward: D = 64)
- *     and dtype BF16 with D = 128.  Anything else returns MOGA_ERR_UNSUPPORTED.
+ *   - Supported: M in [1, 256]; N < 2^31; dtype F32 with D in {64, 128} and dtype BF16 with
+ *     D = 128.  Anything else returns MOGA_ERR_UNSUPPORTED.
  */
 #ifndef MOGA_H_
 #define MOGA_H_

@@ -199,7 +199,7 @@ extern "C" size_t moga_attn_bwd_ws_bytes(int64_t N, int H, int D, int dtype) {
 // Shared launcher.  ts_q / ts_k: NULL (tile lookup inside the kernels, M <= MOGA_MAX_GROUPS) or
 // space for the pre-summed first-tile indices over query rows / key rows (M + 1 ints each).
 static int launch_attn_bwd(const void* d_oh, const void* qh, const void* kh, const void* vh,
-                           const void* oh, const float* lse, int dtype, int64_t Nq, int64_t Nk, int H,
+                           const void* oh, const float* lse, int dtype, int64_t Nq, int64_t Nk, int H, int D,
                            const int32_t* cu_q, const int32_t* cu_k, int32_t* ts_q, int32_t* ts_k,
                            int M, float softmax_scale, void* d_qh, void* d_kh, void* d_vh,
                            float* delta, hipStream_t st) {
@@ -236,24 +236,38 @@ static int launch_attn_bwd(const void* d_oh, const void* qh, const void* kh, con
           (int)tiles, (unsigned short*)d_qh);
     }
   } else {
-    attn_bwd_delta_kernel<16, false><<<(unsigned)((rows * 16 + 255) / 256), 256, 0, st>>>(
-        (const uintx4_t*)d_oh, (const uintx4_t*)oh, lse, rows, 1.f, delta, nullptr);
+    if (D == 64)
+      attn_bwd_delta_kernel<16, false><<<(unsigned)((rows * 16 + 255) / 256), 256, 0, st>>>(
+          (const uintx4_t*)d_oh, (const uintx4_t*)oh, lse, rows, 1.f, delta, nullptr);
+    else
+      attn_bwd_delta_kernel<32, false><<<(unsigned)((rows * 32 + 255) / 256), 256, 0, st>>>(
+          (const uintx4_t*)d_oh, (const uintx4_t*)oh, lse, rows, 1.f, delta, nullptr);
     if (Nk > 0) {
       const int64_t tiles = max_tiles(Nk, M, kF32BM);
       const int64_t blocks = tiles * H;
       if (blocks >= ((int64_t)1 << 31)) return MOGA_ERR_UNSUPPORTED;
       if (ts_k) tile_start_kernel<<<1, 1024, 0, st>>>(cu_k, M, kF32BM, ts_k);
-      attn_bwd_dkdv_f32_kernel<64><<<(unsigned)blocks, 64, 0, st>>>(
-          (const float*)d_oh, (const float*)qh, (const float*)kh, (const float*)vh, lse, delta,
-          cu_q, cu_k, ts_k, M, Nq, Nk, H, softmax_scale, (int)tiles, (float*)d_kh, (float*)d_vh);
+      if (D == 64)
+        attn_bwd_dkdv_f32_kernel<64><<<(unsigned)blocks, 64, 0, st>>>(
+            (const float*)d_oh, (const float*)qh, (const float*)kh, (const float*)vh, lse, delta,
+            cu_q, cu_k, ts_k, M, Nq, Nk, H, softmax_scale, (int)tiles, (float*)d_kh, (float*)d_vh);
+      else
+        attn_bwd_dkdv_f32_kernel<128><<<(unsigned)blocks, 64, 0, st>>>(
+            (const float*)d_oh, (const float*)qh, (const float*)kh, (const float*)vh, lse, delta,
+            cu_q, cu_k, ts_k, M, Nq, Nk, H, softmax_scale, (int)tiles, (float*)d_kh, (float*)d_vh);
     }
     const int64_t tiles = max_tiles(Nq, M, kF32BM);
     const int64_t blocks = tiles * H;
     if (blocks >= ((int64_t)1 << 31)) return MOGA_ERR_UNSUPPORTED;
     if (ts_q) tile_start_kernel<<<1, 1024, 0, st>>>(cu_q, M, kF32BM, ts_q);
-    attn_bwd_dq_f32_kernel<64><<<(unsigned)blocks, 64, 0, st>>>(
-        (const float*)d_oh, (const float*)qh, (const float*)kh, (const float*)vh, lse, delta,
-        cu_q, cu_k, ts_q, M, Nq, Nk, H, softmax_scale, (int)tiles, (float*)d_qh);
+    if (D == 64)
+      attn_bwd_dq_f32_kernel<64><<<(unsigned)blocks, 64, 0, st>>>(
+          (const float*)d_oh, (const float*)qh, (const float*)kh, (const float*)vh, lse, delta,
+          cu_q, cu_k, ts_q, M, Nq, Nk, H, softmax_scale, (int)tiles, (float*)d_qh);
+    else
+      attn_bwd_dq_f32_kernel<128><<<(unsigned)blocks, 64, 0, st>>>(
+          (const float*)d_oh, (const float*)qh, (const float*)kh, (const float*)vh, lse, delta,
+          cu_q, cu_k, ts_q, M, Nq, Nk, H, softmax_scale, (int)tiles, (float*)d_qh);
   }
   return launch_status();
 }
@@ -264,7 +278,7 @@ static int check_attn_bwd_args(int64_t Nq, int64_t Nk, int H, int D, int M, floa
   if (dtype != MOGA_F32 && dtype != MOGA_BF16) return MOGA_ERR_UNSUPPORTED;
   if (Nq >= ((int64_t)1 << 31) || Nk >= ((int64_t)1 << 31)) return MOGA_ERR_UNSUPPORTED;
   if (dtype == MOGA_BF16 && D != 128) return MOGA_ERR_UNSUPPORTED;
-  if (dtype == MOGA_F32 && D != 64) return MOGA_ERR_UNSUPPORTED;
+  if (dtype == MOGA_F32 && D != 64 && D != 128) return MOGA_ERR_UNSUPPORTED;
   return MOGA_OK;
 }
 
@@ -284,7 +298,7 @@ extern "C" int moga_group_attn_bwd(const void* d_oh, const void* qh, const void*
     return MOGA_ERR_INVALID_ARG;
   const size_t need = moga_attn_bwd_ws_bytes(N, H, D, dtype);
   if (!ws || ws_bytes < need) return MOGA_ERR_WORKSPACE;
-  return launch_attn_bwd(d_oh, qh, kh, vh, oh, lse, dtype, N, N, H, cu_seqlens, cu_seqlens, nullptr,
+  return launch_attn_bwd(d_oh, qh, kh, vh, oh, lse, dtype, N, N, H, D, cu_seqlens, cu_seqlens, nullptr,
                          nullptr, M, softmax_scale, d_qh, d_kh, d_vh, (float*)ws, (hipStream_t)stream);
 }
 
@@ -320,6 +334,6 @@ extern "C" int moga_varlen_attn_bwd(const void* d_oh, const void* qh, const void
   if (!ws || ws_bytes < need || !aligned16(ws)) return MOGA_ERR_WORKSPACE;
   int32_t* ts_q = (int32_t*)((char*)ws + round_up(2 * (size_t)Nq * (size_t)H * sizeof(float), 16));
   int32_t* ts_k = ts_q + (G + 1);
-  return launch_attn_bwd(d_oh, qh, kh, vh, oh, lse, dtype, Nq, Nk, H, cu_seqlens_q, cu_seqlens_k, ts_q,
+  return launch_attn_bwd(d_oh, qh, kh, vh, oh, lse, dtype, Nq, Nk, H, D, cu_seqlens_q, cu_seqlens_k, ts_q,
                          ts_k, G, softmax_scale, d_qh, d_kh, d_vh, (float*)ws, st);
 }

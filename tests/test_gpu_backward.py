@@ -78,6 +78,7 @@ def attn_bwd_case(sizes, H, D, dtype, seed):
 @pytest.mark.parametrize("sizes,H,D,dtype", [
     ([512] * 8, 2, 64, "f32"),
     ([1, 0, 65, 130, 31, 0, 64, 200], 2, 64, "f32"),
+    ([100, 0, 3, 67], 2, 128, "f32"),
     ([300, 0, 1, 129, 257, 64, 2, 511], 3, 128, "bf16"),
     ([2049, 1500, 17], 2, 128, "bf16"),
     ([40], 1, 128, "bf16"),
