@@ -17,7 +17,6 @@
 
 namespace moga {
 
-constexpr float kLog2e = 1.4426950408889634f;
 
 // ---------------------------------------------------------------------------------------
 template <int LPR, bool BF16>

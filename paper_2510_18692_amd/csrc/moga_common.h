@@ -65,7 +65,7 @@ __device__ __forceinline__ int other_half_i(int v) { return __shfl_xor(v, 32, kW
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // Zero fill as a kernel (a memset node inside a captured graph is avoided on purpose).
-static __global__ void fill_zero_kernel(float* p, int64_t n) {
+[[maybe_unused]] static __global__ void fill_zero_kernel(float* p, int64_t n) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = 0.f;
 }
