@@ -172,6 +172,22 @@ int moga_fused_attn_fwd(const void* q, const void* k, const void* v, int dtype, 
                         float softmax_scale, void* o, float* lse, void* stream);
 
 /*
+ * Backward of moga_fused_attn_fwd, again without permuted tensors.  d_o [N, H, D] is the gradient of
+ * the gated output o; q, k, v, o token order; lse [H, N] from the fused forward; perm / inv_perm /
+ * cu_seqlens from moga_permute; gate (> 0) from moga_route.  Outputs in token order: d_q, d_k, d_v
+ * [N, H, D] and d_gate [N] fp32 (= sum over heads and channels of d_o * o / gate, the input of
+ * moga_route_bwd).  The gate is folded into the per-row constants of the kernels
+ * (lse - ln gate, rowsum(d_o * o) / gate), so neither the ungated output nor a scaled copy of d_o is
+ * ever written.  BF16, D = 128 only.  Workspace: MOGA_OP_ATTN_BWD.
+ */
+int moga_fused_attn_bwd(const void* d_o, const void* q, const void* k, const void* v, const void* o,
+                        const float* lse, int dtype, int64_t N, int H, int D,
+                        const int32_t* perm, const int32_t* inv_perm, const float* gate,
+                        const int32_t* cu_seqlens, int M, float softmax_scale,
+                        void* d_q, void* d_k, void* d_v, float* d_gate,
+                        void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Attention inside static groups whose queries and keys are listed separately (Section 3.2,
  * "Spatial-Temporal Group Attention": a group's keys and values may hold more rows than its
  * queries, e.g. latent frames added from adjacent shots).  Group g attends the query rows

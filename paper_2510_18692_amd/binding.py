@@ -39,6 +39,8 @@ _SIGNATURES = {
     "moga_route_bwd": (_i32, [_vp, _i32, _vp, _vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _vp, _vp,
                               _sz, _vp]),
     "moga_fused_attn_fwd": (_i32, [_vp, _vp, _vp, _i32, _i64, _i32, _i32, _vp, _vp, _vp, _i32, _f32, _vp, _vp, _vp]),
+    "moga_fused_attn_bwd": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _i64, _i32, _i32, _vp, _vp, _vp, _vp, _i32, _f32,
+                                   _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "moga_varlen_attn_fwd": (_i32, [_vp, _vp, _vp, _i32, _i64, _i64, _i32, _i32, _vp, _vp, _i32, _f32, _vp, _vp,
                                     _vp, _sz, _vp]),
     "moga_varlen_attn_bwd": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _i64, _i64, _i32, _i32, _vp, _vp, _i32,
@@ -241,6 +243,20 @@ def moga_fused_attn_fwd(q, k, v, perm, gate, cu_seqlens, softmax_scale, stream=N
                                     float(softmax_scale), _p(o), _p(lse), _stream(stream))
     _check("moga_fused_attn_fwd", st)
     return o, lse
+
+
+def moga_fused_attn_bwd(d_o, q, k, v, o, lse, perm, inv_perm, gate, cu_seqlens, softmax_scale, stream=None):
+    """Token-order tensors -> (d_q, d_k, d_v [N, H, D], d_gate f32 [N])"""
+    N, H, D = q.shape
+    M = cu_seqlens.shape[0] - 1
+    d_q, d_k, d_v = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    d_gate = torch.empty(N, dtype=torch.float32, device=q.device)
+    ws = _ws(workspace_bytes(OP_ATTN_BWD, N, H, D, M, 0, _dt(q)), q.device)
+    st = load().moga_fused_attn_bwd(_p(d_o), _p(q), _p(k), _p(v), _p(o), _p(lse), _dt(q), N, H, D, _p(perm),
+                                    _p(inv_perm), _p(gate), _p(cu_seqlens), M, float(softmax_scale), _p(d_q),
+                                    _p(d_k), _p(d_v), _p(d_gate), _p(ws), ws.numel(), _stream(stream))
+    _check("moga_fused_attn_bwd", st)
+    return d_q, d_k, d_v, d_gate
 
 
 def moga_varlen_attn_fwd(qh, kh, vh, cu_seqlens_q, cu_seqlens_k, softmax_scale, stream=None):

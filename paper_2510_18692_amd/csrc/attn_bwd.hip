@@ -53,6 +53,67 @@ __global__ __launch_bounds__(256) void attn_bwd_delta_kernel(const uintx4_t* __r
   }
 }
 
+// Pre-pass of the gather-fused backward (bf16, head_dim 128; token-major inputs).  With O = gate * A
+// (Eq. 5) and dO the upstream gradient of O:  delta = rowsum(dA * A) = rowsum(dO * O) =: dot, and the
+// kernels can consume the raw dO rows if the gate is folded into the per-row constants:
+//   P' = gate * P = exp(S - (lse - ln gate)),   dS = P' * (dO V^T - dot / gate),   dV = P'^T dO.
+// Writes, in sorted order [H, N]:  -(lse - ln gate) / scale  and  -dot / gate;  and per token
+// d_gate = sum over heads of dot / gate.  16 tokens per block, 16 lanes per (token, head) row.
+__global__ __launch_bounds__(256) void attn_bwd_fused_prepass_kernel(
+    const uintx4_t* __restrict__ d_o, const uintx4_t* __restrict__ o, const float* __restrict__ lse,
+    const int32_t* __restrict__ inv_perm, const float* __restrict__ gate, int64_t N, int H,
+    float inv_scale, float* __restrict__ neg_lse_over_scale, float* __restrict__ neg_delta,
+    float* __restrict__ d_gate) {
+  __shared__ float s_part[4][16];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int part = lane & 15, rsub = lane >> 4;
+  const int64_t t0 = (int64_t)blockIdx.x * 16;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  int64_t slot[4];
+  float g[4], lg[4];
+  bool ok[4];
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int64_t t = t0 + it * 4 + rsub;
+    ok[it] = t < N;
+    slot[it] = ok[it] ? inv_perm[t] : 0;
+    g[it] = ok[it] ? gate[t] : 1.f;
+    lg[it] = logf(g[it]);
+  }
+  for (int h = wave; h < H; h += 4) {
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      if (!ok[it]) continue;
+      const int64_t t = t0 + it * 4 + rsub;
+      const uintx4_t a = d_o[(t * H + h) * 16 + part], b = o[(t * H + h) * 16 + part];
+      float s = 0.f;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        s = fmaf(bf16_lo_to_f32(a[i]), bf16_lo_to_f32(b[i]), s);
+        s = fmaf(bf16_hi_to_f32(a[i]), bf16_hi_to_f32(b[i]), s);
+      }
+#pragma unroll
+      for (int o2 = 8; o2 > 0; o2 >>= 1) s += __shfl_xor(s, o2, kWave);
+      const float dg = s / g[it];
+      acc[it] += dg;
+      if (part == 0) {
+        const int64_t idx = (int64_t)h * N + slot[it];
+        neg_lse_over_scale[idx] = -(lse[idx] - lg[it]) * inv_scale;
+        neg_delta[idx] = -dg;
+      }
+    }
+  }
+#pragma unroll
+  for (int it = 0; it < 4; ++it)
+    if (part == 0) s_part[wave][it * 4 + rsub] = acc[it];
+  __syncthreads();
+  if (threadIdx.x < 16) {
+    const int64_t t = t0 + threadIdx.x;
+    if (t < N)
+      d_gate[t] = (s_part[0][threadIdx.x] + s_part[1][threadIdx.x]) + (s_part[2][threadIdx.x] + s_part[3][threadIdx.x]);
+  }
+}
+
 // ---------------------------------------------------------------------------------------
 // fp32 (head_dim 64): one thread per row
 // ---------------------------------------------------------------------------------------
@@ -218,7 +279,7 @@ static int launch_attn_bwd(const void* d_oh, const void* qh, const void* kh, con
           (const unsigned short*)vh, lse2, delta, cu_q, cu_k, ts_k, M, Nq, Nk, H, softmax_scale,
           (int)tiles, (unsigned short*)d_kh, (unsigned short*)d_vh);
 #else
-      attn_bwd_dkdv_ab_kernel<<<(unsigned)blocks, 512, 0, st>>>(
+      attn_bwd_dkdv_ab_kernel<false><<<(unsigned)blocks, 512, 0, st>>>(
           (const unsigned short*)d_oh, (const unsigned short*)qh, (const unsigned short*)kh,
           (const unsigned short*)vh, lse2, delta, cu_q, cu_k, ts_k, M, Nq, Nk, H, softmax_scale,
           (int)tiles, (unsigned short*)d_kh, (unsigned short*)d_vh);
@@ -335,4 +396,47 @@ extern "C" int moga_varlen_attn_bwd(const void* d_oh, const void* qh, const void
   int32_t* ts_k = ts_q + (G + 1);
   return launch_attn_bwd(d_oh, qh, kh, vh, oh, lse, dtype, Nq, Nk, H, D, cu_seqlens_q, cu_seqlens_k, ts_q,
                          ts_k, G, softmax_scale, d_qh, d_kh, d_vh, (float*)ws, st);
+}
+
+extern "C" int moga_fused_attn_bwd(const void* d_o, const void* q, const void* k, const void* v,
+                                   const void* o, const float* lse, int dtype, int64_t N, int H, int D,
+                                   const int32_t* perm, const int32_t* inv_perm, const float* gate,
+                                   const int32_t* cu_seqlens, int M, float softmax_scale, void* d_q,
+                                   void* d_k, void* d_v, float* d_gate, void* ws, size_t ws_bytes,
+                                   void* stream) {
+  const int bad = check_attn_bwd_args(N, N, H, D, M, softmax_scale, dtype);
+  if (bad) return bad;
+  if (M > MOGA_MAX_GROUPS || dtype != MOGA_BF16) return MOGA_ERR_UNSUPPORTED;
+  if (N == 0) return MOGA_OK;
+  if (!d_o || !q || !k || !v || !o || !lse || !perm || !inv_perm || !gate || !cu_seqlens || !d_q || !d_k ||
+      !d_v || !d_gate)
+    return MOGA_ERR_INVALID_ARG;
+  if (!(aligned16(d_o) && aligned16(q) && aligned16(k) && aligned16(v) && aligned16(o) && aligned16(d_q) &&
+        aligned16(d_k) && aligned16(d_v)))
+    return MOGA_ERR_INVALID_ARG;
+  const size_t need = moga_attn_bwd_ws_bytes(N, H, D, dtype);
+  if (!ws || ws_bytes < need) return MOGA_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  float* delta = (float*)ws;
+  float* lse2 = delta + N * (int64_t)H;
+  attn_bwd_fused_prepass_kernel<<<(unsigned)((N + 15) / 16), 256, 0, st>>>(
+      (const uintx4_t*)d_o, (const uintx4_t*)o, lse, inv_perm, gate, N, H, 1.f / softmax_scale, lse2, delta, d_gate);
+  {
+    const int64_t tiles = max_tiles(N, M, 128);
+    const int64_t blocks = (tiles * H + 7) / 8 * 8;
+    if (blocks >= ((int64_t)1 << 31)) return MOGA_ERR_UNSUPPORTED;
+    attn_bwd_dkdv_ab_kernel<true><<<(unsigned)blocks, 512, 0, st>>>(
+        (const unsigned short*)d_o, (const unsigned short*)q, (const unsigned short*)k, (const unsigned short*)v,
+        lse2, delta, cu_seqlens, cu_seqlens, nullptr, M, N, N, H, softmax_scale, (int)tiles, (unsigned short*)d_k,
+        (unsigned short*)d_v, perm);
+  }
+  {
+    const int64_t tiles = max_tiles(N, M, 256);
+    const int64_t blocks = (tiles * H + 7) / 8 * 8;
+    attn_bwd_dq_pipe_kernel<8, 1, true><<<(unsigned)blocks, 512, 0, st>>>(
+        (const unsigned short*)d_o, (const unsigned short*)q, (const unsigned short*)k, (const unsigned short*)v,
+        lse2, delta, cu_seqlens, cu_seqlens, nullptr, M, N, N, H, softmax_scale, (int)tiles, (unsigned short*)d_q,
+        perm);
+  }
+  return launch_status();
 }

@@ -153,14 +153,18 @@ __device__ __forceinline__ void dq_tile(const DqLane& ln, unsigned off, const bf
   dq_accumulate<QW, SOFF + 8192>(ln, off, dsf_b, dq);
 }
 
-template <int NW, int QW>
+// GATHER (both backward kernels): d_oh, qh, kh, vh and the gradient outputs are token-major
+// [N, H, 128] and row j of a group is token perm[j]; neg_lse_over_scale / neg_delta stay in
+// sorted order [H, N] and carry the gate (see attn_bwd_fused_prepass_kernel), so d_oh is the
+// raw upstream gradient of the gated output.
+template <int NW, int QW, bool GATHER = false>
 __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_pipe_kernel(
     const unsigned short* __restrict__ d_oh, const unsigned short* __restrict__ qh,
     const unsigned short* __restrict__ kh, const unsigned short* __restrict__ vh,
     const float* __restrict__ neg_lse_over_scale, const float* __restrict__ neg_delta,
     const int32_t* __restrict__ cu_q, const int32_t* __restrict__ cu_k,
     const int32_t* __restrict__ tile_start, int M, int64_t Nq, int64_t Nk, int H, float scale,
-    int tiles_per_head, unsigned short* __restrict__ d_qh) {
+    int tiles_per_head, unsigned short* __restrict__ d_qh, const int32_t* __restrict__ perm = nullptr) {
   constexpr int BM = NW * 32 * QW;
   constexpr int kDmaPerTile = 2 * (16 / NW);
   __shared__ __attribute__((aligned(1024))) unsigned short Ks[kPipeNBuf][64 * kHeadDim];
@@ -194,7 +198,8 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_pipe_kernel(
     for (int qw = 0; qw < QW; ++qw) {
       const int qrow = q0 + (wave * QW + qw) * 32 + r;
       if (qrow < ge) {
-        uintx4_t* op = (uintx4_t*)(d_qh + (head_off + qrow) * kHeadDim + 64 * h);
+        const int64_t orow = GATHER ? (int64_t)perm[qrow] * H + head : head_off + qrow;
+        uintx4_t* op = (uintx4_t*)(d_qh + orow * kHeadDim + 64 * h);
         const uintx4_t z = {0u, 0u, 0u, 0u};
 #pragma unroll
         for (int i = 0; i < 8; ++i) op[i] = z;
@@ -209,8 +214,9 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_pipe_kernel(
   for (int qw = 0; qw < QW; ++qw) {
     int qrow = q0 + (wave * QW + qw) * 32 + r;
     if (qrow > ge - 1) qrow = ge - 1;
-    const unsigned short* qp = qh + (head_off + qrow) * kHeadDim + 8 * h;
-    const unsigned short* dp = d_oh + (head_off + qrow) * kHeadDim + 8 * h;
+    const int64_t irow = GATHER ? (int64_t)perm[qrow] * H + head : head_off + qrow;
+    const unsigned short* qp = qh + irow * kHeadDim + 8 * h;
+    const unsigned short* dp = d_oh + irow * kHeadDim + 8 * h;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
       qf[qw][ks] = *(const bf16x8_t*)(qp + 16 * ks);
@@ -221,15 +227,21 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_pipe_kernel(
   }
 
   PipeDma dma;
-  dma.kbase = uniform_ptr(kh + (head_off_k + gs) * kHeadDim);
-  dma.vbase = uniform_ptr(vh + (head_off_k + gs) * kHeadDim);
+  dma.kbase = uniform_ptr(GATHER ? kh + (int64_t)head * kHeadDim : kh + (head_off_k + gs) * kHeadDim);
+  dma.vbase = uniform_ptr(GATHER ? vh + (int64_t)head * kHeadDim : vh + (head_off_k + gs) * kHeadDim);
   dma.lds_k = lds_addr_uniform(&Ks[0][0]) + wave * 1024;
   dma.lds_v = lds_addr_uniform(&Vs[0][0]) + wave * 1024;
   dma.row0 = 4 * wave + (lane >> 4);
   dma.chunk_off = (unsigned)(((lane & 15) ^ lds_swizzle(dma.row0)) * 16);
   dma.last_row = n - 1;
+  if (GATHER) {
+    dma.rows = (const int32_t*)uniform_ptr(perm + gs);
+    dma.tok_stride = (int64_t)H * kHeadDim * 2;
+    dma.wave_row = 4 * wave;
+    pipe_load_tokens<NW>(dma, 0);
+  }
 #pragma unroll
-  for (int t = 0; t <= kPipeAhead; ++t) pipe_issue_tile<NW>(dma, 64 * t, t);
+  for (int t = 0; t <= kPipeAhead; ++t) pipe_issue<NW, GATHER>(dma, 64 * t, t);
 
   DqLane ln;
   {
@@ -267,7 +279,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_pipe_kernel(
 #define MOGA_DQ_TILE(B)                                                                  \
   __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * kPipeAhead));                      \
   __syncthreads();                                                                       \
-  pipe_issue_tile<NW>(dma, 64 * (T + (B) + 1 + kPipeAhead), ((B) + 1 + kPipeAhead) & 3); \
+  pipe_issue<NW, GATHER>(dma, 64 * (T + (B) + 1 + kPipeAhead), ((B) + 1 + kPipeAhead) & 3); \
   dq_tile<QW, false, (B) * kPipeTileBytes>(ln, 0, qf, dof, lq, dl, dq, c, h, 64);
   for (; T + 4 <= nfull; T += 4) {   // four tiles per iteration: every LDS offset is an immediate
     MOGA_DQ_TILE(0)
@@ -279,7 +291,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_pipe_kernel(
   for (; T < nfull; ++T) {
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * kPipeAhead));
     __syncthreads();
-    pipe_issue_tile<NW>(dma, 64 * (T + 1 + kPipeAhead), (T + 1 + kPipeAhead) & 3);
+    pipe_issue<NW, GATHER>(dma, 64 * (T + 1 + kPipeAhead), (T + 1 + kPipeAhead) & 3);
     dq_tile<QW, false, 0>(ln, ((unsigned)T & 3u) * kPipeTileBytes, qf, dof, lq, dl, dq, c, h, 64);
   }
   if (n & 63) {   // last, partial tile: masked keys contribute zero
@@ -293,7 +305,8 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_pipe_kernel(
   for (int qw = 0; qw < QW; ++qw) {
     const int qrow = q0 + (wave * QW + qw) * 32 + r;
     if (qrow < ge) {
-      unsigned short* op = d_qh + (head_off + qrow) * kHeadDim + 4 * h;
+      const int64_t orow = GATHER ? (int64_t)perm[qrow] * H + head : head_off + qrow;
+      unsigned short* op = d_qh + orow * kHeadDim + 4 * h;
 #pragma unroll
       for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
@@ -704,13 +717,15 @@ __device__ __forceinline__ void ab_tile(const AbLane& ln, int role, unsigned off
   ab_accumulate(tr1, bop[1], acc);
 }
 
+template <bool GATHER = false>
 __global__ __launch_bounds__(512) void attn_bwd_dkdv_ab_kernel(
     const unsigned short* __restrict__ d_oh, const unsigned short* __restrict__ qh,
     const unsigned short* __restrict__ kh, const unsigned short* __restrict__ vh,
     const float* __restrict__ neg_lse_over_scale, const float* __restrict__ neg_delta,
     const int32_t* __restrict__ cu_q, const int32_t* __restrict__ cu_k,
     const int32_t* __restrict__ tile_start, int M, int64_t Nq, int64_t Nk, int H, float scale,
-    int tiles_per_head, unsigned short* __restrict__ d_kh, unsigned short* __restrict__ d_vh) {
+    int tiles_per_head, unsigned short* __restrict__ d_kh, unsigned short* __restrict__ d_vh,
+    const int32_t* __restrict__ perm = nullptr) {
   constexpr int NW = 8;
   constexpr int BK = 128;                          // 4 pairs of waves x 32 keys
   constexpr int kDmaPerTile = 2 * (16 / NW) + 2;
@@ -751,7 +766,8 @@ __global__ __launch_bounds__(512) void attn_bwd_dkdv_ab_kernel(
 
   if (n <= 0) {   // keys without queries: zero gradient (block-uniform branch)
     if (krow < ge) {
-      uintx4_t* o4 = (uintx4_t*)(outp + (head_off + krow) * kHeadDim + 64 * h);
+      const int64_t orow = GATHER ? (int64_t)perm[krow] * H + head : head_off + krow;
+      uintx4_t* o4 = (uintx4_t*)(outp + orow * kHeadDim + 64 * h);
       const uintx4_t z = {0u, 0u, 0u, 0u};
 #pragma unroll
       for (int i = 0; i < 8; ++i) o4[i] = z;
@@ -763,25 +779,32 @@ __global__ __launch_bounds__(512) void attn_bwd_dkdv_ab_kernel(
   const int krow_c = krow < ge ? krow : ge - 1;
   bf16x8_t kvf[8];
   {
-    const unsigned short* kp = (role == 0 ? kh : vh) + (head_off + krow_c) * kHeadDim + 8 * h;
+    const int64_t irow = GATHER ? (int64_t)perm[krow_c] * H + head : head_off + krow_c;
+    const unsigned short* kp = (role == 0 ? kh : vh) + irow * kHeadDim + 8 * h;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) kvf[ks] = *(const bf16x8_t*)(kp + 16 * ks);
   }
 
   PipeDma dma;   // "k" = Q rows, "v" = dO rows of this head's group
-  dma.kbase = uniform_ptr(qh + (head_off_q + gs) * kHeadDim);
-  dma.vbase = uniform_ptr(d_oh + (head_off_q + gs) * kHeadDim);
+  dma.kbase = uniform_ptr(GATHER ? qh + (int64_t)head * kHeadDim : qh + (head_off_q + gs) * kHeadDim);
+  dma.vbase = uniform_ptr(GATHER ? d_oh + (int64_t)head * kHeadDim : d_oh + (head_off_q + gs) * kHeadDim);
   dma.lds_k = lds_addr_uniform(&Qs[0][0]) + wave * 1024;
   dma.lds_v = lds_addr_uniform(&dOs[0][0]) + wave * 1024;
   dma.row0 = 4 * wave + (lane >> 4);
   dma.chunk_off = (unsigned)(((lane & 15) ^ lds_swizzle(dma.row0)) * 16);
   dma.last_row = n - 1;
+  if (GATHER) {
+    dma.rows = (const int32_t*)uniform_ptr(perm + gs);
+    dma.tok_stride = (int64_t)H * kHeadDim * 2;
+    dma.wave_row = 4 * wave;
+    pipe_load_tokens<NW>(dma, 0);
+  }
   const void* lbase = uniform_ptr(neg_lse_over_scale + head_off_q + gs);
   const void* dbase = uniform_ptr(neg_delta + head_off_q + gs);
   const unsigned lds_l = lds_addr_uniform(&Ls[0][0]), lds_d = lds_addr_uniform(&Ds[0][0]);
   auto issue_tile = [&](int T) {   // every wave issues the (identical) row-constant loads so that all count alike
     const int slot = T & 3;
-    pipe_issue_tile<NW>(dma, 64 * T, slot);
+    pipe_issue<NW, GATHER>(dma, 64 * T, slot);
     const unsigned roff = (unsigned)min(64 * T + lane, n - 1) * 4u;
     lds_dma4_soff(lbase, roff, lds_l + slot * 256);
     lds_dma4_soff(dbase, roff, lds_d + slot * 256);
@@ -846,7 +869,8 @@ __global__ __launch_bounds__(512) void attn_bwd_dkdv_ab_kernel(
   __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // drain the look-ahead loads before the LDS is released
   if (krow < ge) {
     const float f = role == 0 ? 1.f : scale;
-    unsigned short* op = outp + (head_off + krow) * kHeadDim + 4 * h;
+    const int64_t orow = GATHER ? (int64_t)perm[krow] * H + head : head_off + krow;
+    unsigned short* op = outp + orow * kHeadDim + 4 * h;
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
