@@ -238,6 +238,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_pipe_kernel(
     dma.rows = (const int32_t*)uniform_ptr(perm + gs);
     dma.tok_stride = (int64_t)H * kHeadDim * 2;
     dma.wave_row = 4 * wave;
+    dma.last_index = (int)(Nk - 1) - gs;
     pipe_load_tokens<NW>(dma, 0);
   }
 #pragma unroll
@@ -797,6 +798,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dkdv_ab_kernel(
     dma.rows = (const int32_t*)uniform_ptr(perm + gs);
     dma.tok_stride = (int64_t)H * kHeadDim * 2;
     dma.wave_row = 4 * wave;
+    dma.last_index = (int)(Nq - 1) - gs;
     pipe_load_tokens<NW>(dma, 0);
   }
   const void* lbase = uniform_ptr(neg_lse_over_scale + head_off_q + gs);

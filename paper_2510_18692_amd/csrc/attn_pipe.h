@@ -151,6 +151,8 @@ struct PipeDma {
   const int32_t* rows;     // index list at the group's first row (wave-uniform)
   int64_t tok_stride;      // bytes between two tokens
   int wave_row;            // 4 * wave (wave-uniform)
+  int last_index;          // last readable entry of `rows` (the list ends there; entries past the
+                           // group's own rows belong to other groups and are harmless: those rows are masked)
   // tokens of the rows this wave moves in the next tile to be issued, rounds 0 and 1 (wave-uniform;
   // separate scalars so that they stay in scalar registers)
   int ta0, ta1, ta2, ta3, tb0, tb1, tb2, tb3;
@@ -179,9 +181,29 @@ __device__ __forceinline__ int scalar_load_index(const int32_t* p, int i) {
   return __builtin_amdgcn_readfirstlane(((cptr)(uintptr_t)p)[i]);
 }
 
+typedef int intx4_t __attribute__((ext_vector_type(4)));
+
+// Four consecutive indices with one 16-byte scalar load.
+__device__ __forceinline__ intx4_t scalar_load_index4(const int32_t* p, int i) {
+  typedef const intx4_t __attribute__((address_space(4), aligned(4))) * cptr4;
+  return *(cptr4)(uintptr_t)(p + i);
+}
+
 template <int NW>
 __device__ __forceinline__ void pipe_load_tokens(PipeDma& d, int kv0) {
   const int r0 = kv0 + d.wave_row;
+  if (NW == 8 && r0 + 35 <= d.last_index) {   // the common case: two 16-byte scalar loads, no clamping
+    const intx4_t a = scalar_load_index4(d.rows, r0), b = scalar_load_index4(d.rows, r0 + 32);
+    d.ta0 = __builtin_amdgcn_readfirstlane(a[0]);
+    d.ta1 = __builtin_amdgcn_readfirstlane(a[1]);
+    d.ta2 = __builtin_amdgcn_readfirstlane(a[2]);
+    d.ta3 = __builtin_amdgcn_readfirstlane(a[3]);
+    d.tb0 = __builtin_amdgcn_readfirstlane(b[0]);
+    d.tb1 = __builtin_amdgcn_readfirstlane(b[1]);
+    d.tb2 = __builtin_amdgcn_readfirstlane(b[2]);
+    d.tb3 = __builtin_amdgcn_readfirstlane(b[3]);
+    return;
+  }
   d.ta0 = scalar_load_index(d.rows, min(r0 + 0, d.last_row));
   d.ta1 = scalar_load_index(d.rows, min(r0 + 1, d.last_row));
   d.ta2 = scalar_load_index(d.rows, min(r0 + 2, d.last_row));
@@ -309,6 +331,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_bf16_pipe_kernel(
     dma.rows = (const int32_t*)uniform_ptr(perm + gs);
     dma.tok_stride = (int64_t)H * kHeadDim * 2;
     dma.wave_row = 4 * wave;
+    dma.last_index = (int)(Nk - 1) - gs;
     pipe_load_tokens<NW>(dma, 0);
   }
 #pragma unroll
