@@ -43,6 +43,9 @@ def parse():
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="C4b", help="C1, C1b, C2, C3, C3b, C4, C4b (default), C5")
+    ap.add_argument("--fused", action="store_true",
+                    help="use the gather-fused attention calls (no permuted tensors are materialised): permute builds "
+                         "the index only, moga_fused_attn_fwd / _bwd replace gather + attention + scatter")
     ap.add_argument("--graph", action="store_true",
                     help="record one step into a HIP graph and time its replays (whole-step time only; for the "
                          "small, launch-bound workloads)")
@@ -80,6 +83,9 @@ def algorithmic_work(w, counts):
             "moga_permute_bwd": ("hbm", 6 * t + 4 * N),
             "moga_route_bwd": ("hbm", N * d * es + 4 * N * M + 16 * N + M * d * 4),
         })
+    work["moga_fused_attn_fwd"] = work["moga_group_attn_fwd"]
+    if w.backward:
+        work["moga_fused_attn_bwd"] = work["moga_group_attn_bwd"]
     return work
 
 
@@ -202,6 +208,34 @@ def main():
     names = ["moga_route", "moga_permute", "moga_group_attn_fwd", "moga_unpermute"]
     if w.backward:
         names += ["moga_unpermute_bwd", "moga_group_attn_bwd", "moga_permute_bwd", "moga_route_bwd"]
+    if args.fused:
+        if w.dtype != "bf16":
+            print("bench.py: --fused needs a bf16 workload", file=sys.stderr)
+            sys.exit(2)
+        names = ["moga_route", "moga_permute", "moga_fused_attn_fwd"]
+        if w.backward:
+            names += ["moga_fused_attn_bwd", "moga_route_bwd"]
+
+    def step_fused(events=None):
+        def mark(i):
+            if events is not None:
+                events[i].record()
+        mark(0)
+        group, gate, probs, _ = mg.moga_route(X, W, want_probs=w.backward)
+        mark(1)
+        pm = mg.moga_permute(group, w.M)
+        mark(2)
+        o, lse = mg.moga_fused_attn_fwd(Q, K, V, pm["perm"], gate, pm["cu_seqlens"], w.scale)
+        mark(3)
+        out = {"counts": pm["counts"], "o": o}
+        if w.backward:
+            d_q, d_k, d_v, d_gate = mg.moga_fused_attn_bwd(dO, Q, K, V, o, lse, pm["perm"], pm["inv_perm"], gate,
+                                                           pm["cu_seqlens"], w.scale)
+            mark(4)
+            d_w, _ = mg.moga_route_bwd(X, W, probs, group, gate, d_gate)
+            mark(5)
+            out["d_w"] = d_w
+        return out
 
     def step(events=None):
         def mark(i):
@@ -230,6 +264,8 @@ def main():
             out["d_w"] = d_w
         return out
 
+    if args.fused:
+        step = step_fused
     if args.calibrate_copy:
         a = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
         b = torch.empty_like(a)
@@ -306,7 +342,8 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": f"{w.name}: N={w.N} ({w.grid} latent grid), H={w.H}, D={w.D}, "
                                f"d_model={w.d_model}, M={w.M}, {w.hidden} hidden states, "
-                               + ("forward+backward" if w.backward else "forward"),
+                               + ("forward+backward" if w.backward else "forward")
+                               + (", gather-fused attention calls" if args.fused else ""),
                    "group_sizes": {"min": min(counts), "max": max(counts),
                                    "sum_sq_over_N2": round(flops.sum_sq(counts) / float(w.N) ** 2, 5)}},
         "roofline": roof,
