@@ -95,3 +95,30 @@ def test_invalid_arguments_return_status_codes_without_a_gpu():
     assert lib.moga_balance_loss_bwd(fake, None, 64, 8, 0.1, 1.0, 0, fake, None) == -1
     assert lib.moga_balance_loss_bwd(fake, fake, 0, 8, 0.1, 1.0, 0, fake, None) == 0
     assert binding.workspace_bytes(binding.OP_BALANCE_LOSS, 4096, 0, 0, 32, 0, 0) >= 32 * 12
+
+
+def test_new_entry_points_validate_arguments_without_a_gpu():
+    lib = binding.load()
+    fake = ctypes.c_void_p(0x1000)
+    # attention with separate query / key lists: bad scale, unsupported head_dim, missing workspace
+    assert lib.moga_varlen_attn_fwd(fake, fake, fake, 1, 64, 64, 2, 128, fake, fake, 3, 0.0, fake, fake, fake, 64, None) == -1
+    assert lib.moga_varlen_attn_fwd(fake, fake, fake, 1, 64, 64, 2, 96, fake, fake, 3, 0.1, fake, fake, fake, 64, None) == -2
+    assert lib.moga_varlen_attn_fwd(fake, fake, fake, 1, 64, 64, 2, 128, fake, fake, 3, 0.1, fake, fake, None, 0, None) == -3
+    assert lib.moga_varlen_attn_fwd(fake, fake, fake, 1, 0, 64, 2, 128, fake, fake, 3, 0.1, fake, fake, None, 0, None) == 0
+    assert lib.moga_varlen_attn_bwd(fake, fake, fake, fake, fake, fake, 1, 64, 64, 2, 128, fake, fake, 3, 0.1,
+                                    fake, fake, fake, fake, 8, None) == -3
+    # gather-fused calls: bf16 only, at most MOGA_MAX_GROUPS groups
+    assert lib.moga_fused_attn_fwd(fake, fake, fake, 0, 64, 2, 64, fake, fake, fake, 4, 0.1, fake, fake, None) == -2
+    assert lib.moga_fused_attn_fwd(fake, fake, fake, 1, 64, 2, 128, fake, fake, fake, 300, 0.1, fake, fake, None) == -2
+    assert lib.moga_fused_attn_fwd(fake, fake, fake, 1, 64, 2, 128, None, fake, fake, 4, 0.1, fake, fake, None) == -1
+    assert lib.moga_fused_attn_bwd(fake, fake, fake, fake, fake, fake, 1, 64, 2, 128, fake, fake, fake, fake, 4, 0.1,
+                                   fake, fake, fake, fake, None, 0, None) == -3
+    # row movement of the static branches
+    assert lib.moga_gather_rows(fake, 1, None, 10, 2, 128, fake, None) == -1
+    assert lib.moga_gather_rows(fake, 1, fake, 10, 2, 100, fake, None) == -2
+    assert lib.moga_gather_rows_bwd(fake, 1, None, fake, 10, 12, 2, 128, 0, fake, None) == -1
+    assert lib.moga_merge3_fwd(fake, fake, None, 1, None, None, None, fake, 10, 2, 128, fake, None) == -1
+    assert lib.moga_merge3_bwd(fake, fake, 1, None, None, None, fake, 10, 2, 128, fake, fake, fake, None, None) == -1
+    wb = binding.workspace_bytes
+    assert wb(binding.OP_VARLEN_ATTN_FWD, 1000, 2, 128, 500, 0, 1) >= 501 * 4
+    assert wb(binding.OP_VARLEN_ATTN_BWD, 1000, 2, 128, 500, 0, 1) >= 2 * 1000 * 2 * 4 + 2 * 501 * 4
