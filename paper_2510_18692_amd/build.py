@@ -10,6 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmoga.so")
+EXAMPLE = os.path.join(HERE, "c_abi_example")
 SOURCES = ["api.hip", "route.hip", "permute.hip", "attn_fwd.hip", "attn_bwd.hip", "balance.hip", "static_index.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=default",
@@ -50,6 +51,12 @@ def build(verbose: bool = False, extra_flags=()) -> str:
                        capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stdout + r.stderr)
+    # a torch-free client of the C ABI (run by the GPU tests)
+    r = subprocess.run([hipcc, "--offload-arch=gfx950", "-O2", "-I", os.path.join(ROOT, "include"),
+                        os.path.join(CSRC, "c_abi_example.cpp"), "-L", HERE, "-lmoga", "-Wl,-rpath,$ORIGIN",
+                        "-o", EXAMPLE], capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("example build failed:\n" + r.stdout + r.stderr)
     return LIB
 
 
