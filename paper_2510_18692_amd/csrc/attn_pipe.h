@@ -240,7 +240,7 @@ __device__ __forceinline__ void pipe_issue_tile_gather(PipeDma& d, int kv0, int 
 
 template <int NW, bool GATHER>
 __device__ __forceinline__ void pipe_issue(PipeDma& d, int kv0, int buf) {
-  if (GATHER) pipe_issue_tile_gather<NW>(d, kv0, buf);
+  if constexpr (GATHER) pipe_issue_tile_gather<NW>(d, kv0, buf);
   else pipe_issue_tile<NW>(d, kv0, buf);
 }
 
@@ -327,7 +327,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_bf16_pipe_kernel(
   dma.row0 = 4 * wave + (lane >> 4);
   dma.chunk_off = (unsigned)(((lane & 15) ^ lds_swizzle(dma.row0)) * 16);
   dma.last_row = n - 1;
-  if (GATHER) {
+  if constexpr (GATHER) {
     dma.rows = (const int32_t*)uniform_ptr(perm + gs);
     dma.tok_stride = (int64_t)H * kHeadDim * 2;
     dma.wave_row = 4 * wave;
