@@ -88,8 +88,10 @@ __global__ __launch_bounds__(256) void route_generic_kernel(
 // ---------------------------------------------------------------------------------------
 // bf16 MFMA path (M <= 32, d_model % 64 == 0)
 // ---------------------------------------------------------------------------------------
-constexpr int kRouteKC = 256;              // k-chunk of W staged in LDS
+constexpr int kRouteKC = 128;              // k-chunk of W staged in LDS (two 64-wide k blocks)
 constexpr int kRouteStride = kRouteKC + 8; // bf16 elements per LDS row (+16 B against bank conflicts)
+// float4 loads of W per thread and chunk in a block of NWV waves
+template <int NWV> constexpr int kRouteWLoads = 32 * (kRouteKC / 4) / (64 * NWV);
 
 // Split an fp32 value into three bf16 limbs whose sum is exactly the value.
 __device__ __forceinline__ void split3(float w, unsigned short& hi, unsigned short& mid,
@@ -101,15 +103,86 @@ __device__ __forceinline__ void split3(float w, unsigned short& hi, unsigned sho
   lo = f32_to_bf16_bits(r2);
 }
 
-template <int TT>  // 32-token tiles per wave
-__global__ __launch_bounds__(256, 2) void route_mfma_kernel(
+// One thread's share of a weight chunk: rows of W beyond M and columns beyond d read as zero.
+template <int NWV>
+__device__ __forceinline__ void route_load_w(const float* __restrict__ w, int d, int M, int k0,
+                                             floatx4_t (&wv)[kRouteWLoads<NWV>]) {
+#pragma unroll
+  for (int i = 0; i < kRouteWLoads<NWV>; ++i) {
+    const int idx = threadIdx.x + 64 * NWV * i;
+    const int row = idx / (kRouteKC / 4), c = (idx % (kRouteKC / 4)) * 4;
+    const floatx4_t z = {0.f, 0.f, 0.f, 0.f};
+    wv[i] = (row < M && k0 + c < d) ? *(const floatx4_t*)(w + (int64_t)row * d + k0 + c) : z;
+  }
+}
+
+template <int NWV>
+__device__ __forceinline__ void route_store_w(unsigned short (&sw)[3][32][kRouteStride],
+                                              const floatx4_t (&wv)[kRouteWLoads<NWV>]) {
+#pragma unroll
+  for (int i = 0; i < kRouteWLoads<NWV>; ++i) {
+    const int idx = threadIdx.x + 64 * NWV * i;
+    const int row = idx / (kRouteKC / 4), c = (idx % (kRouteKC / 4)) * 4;
+    unsigned short hi[4], mid[4], lo[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) split3(wv[i][e], hi[e], mid[e], lo[e]);
+    const uintx2_t ph = {hi[0] | ((unsigned)hi[1] << 16), hi[2] | ((unsigned)hi[3] << 16)};
+    const uintx2_t pm = {mid[0] | ((unsigned)mid[1] << 16), mid[2] | ((unsigned)mid[3] << 16)};
+    const uintx2_t pl = {lo[0] | ((unsigned)lo[1] << 16), lo[2] | ((unsigned)lo[3] << 16)};
+    *(uintx2_t*)&sw[0][row][c] = ph;
+    *(uintx2_t*)&sw[1][row][c] = pm;
+    *(uintx2_t*)&sw[2][row][c] = pl;
+  }
+}
+
+// A 64-wide k block of X as a wave's MFMA B operands: lane half h holds elements [32h, 32h+32) of
+// its token's row as four 16-byte pieces; piece s feeds MFMA k-step s (the weight operand uses
+// the same map).
+template <int TT>
+struct RouteXBlock {
+  uintx4_t v[TT][4];
+};
+
+template <int TT>
+__device__ __forceinline__ void route_load_x(RouteXBlock<TT>& b, const unsigned short* const (&xrow)[TT],
+                                             int koff) {
+#pragma unroll
+  for (int t = 0; t < TT; ++t)
+#pragma unroll
+    for (int s = 0; s < 4; ++s) b.v[t][s] = *(const uintx4_t*)(xrow[t] + koff + 8 * s);
+}
+
+template <int TT>
+__device__ __forceinline__ void route_mfma_block(floatx16_t (&acc)[TT],
+                                                 const unsigned short (&sw)[3][32][kRouteStride],
+                                                 int col0, int r, int h, const RouteXBlock<TT>& b) {
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+#pragma unroll
+    for (int limb = 0; limb < 3; ++limb) {
+      const bf16x8_t a = *(const bf16x8_t*)&sw[limb][r][col0 + 32 * h + 8 * s];
+#pragma unroll
+      for (int t = 0; t < TT; ++t)
+        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+            a, __builtin_bit_cast(bf16x8_t, b.v[t][s]), acc[t], 0, 0, 0);
+    }
+  }
+}
+
+// The weight chunk is double-buffered: while the matrix cores work on chunk c, the fp32 weights of
+// chunk c+1 are in flight from L2; they are split and stored after the chunk's MFMAs, one block
+// barrier per chunk.  X lives in a ring of four k-block register sets with fixed roles (the loop
+// is unrolled over two chunks, so no set is ever copied): a set is refilled, four k blocks ahead,
+// right after its MFMAs, which keeps 16-32 KB of loads per wave in flight across the barriers.
+template <int TT, int NWV>  // 32-token tiles per wave, waves per block
+__global__ __launch_bounds__(64 * NWV, 8 / NWV) void route_mfma_kernel(
     const unsigned short* __restrict__ x, const float* __restrict__ w,
     const float* __restrict__ bias, int64_t N, int d, int M, int32_t* __restrict__ group,
     float* __restrict__ gate, float* __restrict__ probs, float* __restrict__ logits) {
-  __shared__ __attribute__((aligned(16))) unsigned short s_w[3][32][kRouteStride];
+  __shared__ __attribute__((aligned(16))) unsigned short s_w[2][3][32][kRouteStride];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int r = lane & 31, h = lane >> 5;
-  const int64_t tok0 = ((int64_t)blockIdx.x * 4 + wave) * (32 * TT);
+  const int64_t tok0 = ((int64_t)blockIdx.x * NWV + wave) * (32 * TT);
 
   const unsigned short* xrow[TT];
 #pragma unroll
@@ -125,71 +198,45 @@ __global__ __launch_bounds__(256, 2) void route_mfma_kernel(
 #pragma unroll
     for (int v = 0; v < 16; ++v) total[t][v] = 0.f;
 
-  // Within a 64-wide k block, lane half h reads elements [32h, 32h+32) of its row as four
-  // 16-byte pieces; piece s feeds MFMA k-step s.  The weight operand uses the same map.
-  uintx4_t xb[TT][4];
-#pragma unroll
-  for (int t = 0; t < TT; ++t)
-#pragma unroll
-    for (int s = 0; s < 4; ++s) xb[t][s] = *(const uintx4_t*)(xrow[t] + 8 * s);
+  // k blocks past the end of the row are clamped to the last one (loaded, never used)
+  const int last_kb = d - 64;
+  RouteXBlock<TT> b0, b1, b2, b3;
+  route_load_x<TT>(b0, xrow, 0);
+  route_load_x<TT>(b1, xrow, min(64, last_kb));
+  route_load_x<TT>(b2, xrow, min(128, last_kb));
+  route_load_x<TT>(b3, xrow, min(192, last_kb));
+  floatx4_t wv[kRouteWLoads<NWV>];
+  route_load_w<NWV>(w, d, M, 0, wv);
+  route_store_w<NWV>(s_w[0], wv);
+  __syncthreads();
 
-  for (int k0 = 0; k0 < d; k0 += kRouteKC) {
-    const int kc = min(kRouteKC, d - k0);
-    __syncthreads();
-    const int q4 = kc >> 2;
-    for (int idx = threadIdx.x; idx < 32 * q4; idx += 256) {
-      const int row = idx / q4, c = (idx - row * q4) * 4;
-      floatx4_t wv = {0.f, 0.f, 0.f, 0.f};
-      if (row < M) wv = *(const floatx4_t*)(w + (int64_t)row * d + k0 + c);
-      unsigned short hi[4], mid[4], lo[4];
-#pragma unroll
-      for (int e = 0; e < 4; ++e) split3(wv[e], hi[e], mid[e], lo[e]);
-      uintx2_t ph = {hi[0] | ((unsigned)hi[1] << 16), hi[2] | ((unsigned)hi[3] << 16)};
-      uintx2_t pm = {mid[0] | ((unsigned)mid[1] << 16), mid[2] | ((unsigned)mid[3] << 16)};
-      uintx2_t pl = {lo[0] | ((unsigned)lo[1] << 16), lo[2] | ((unsigned)lo[3] << 16)};
-      *(uintx2_t*)&s_w[0][row][c] = ph;
-      *(uintx2_t*)&s_w[1][row][c] = pm;
-      *(uintx2_t*)&s_w[2][row][c] = pl;
-    }
-    __syncthreads();
-
-    floatx16_t acc[TT];
-#pragma unroll
-    for (int t = 0; t < TT; ++t)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
-
-    for (int kb = 0; kb < kc; kb += 64) {
-      // prefetch the next 64-wide block of X (clamped to the row's last block at the very end)
-      uintx4_t xn[TT][4];
-      const int knext = min(k0 + kb + 64, d - 64);
-#pragma unroll
-      for (int t = 0; t < TT; ++t)
-#pragma unroll
-        for (int s = 0; s < 4; ++s) xn[t][s] = *(const uintx4_t*)(xrow[t] + knext + 8 * s);
-#pragma unroll
-      for (int s = 0; s < 4; ++s) {
-#pragma unroll
-        for (int limb = 0; limb < 3; ++limb) {
-          const bf16x8_t a = *(const bf16x8_t*)&s_w[limb][r][kb + 32 * h + 8 * s];
-#pragma unroll
-          for (int t = 0; t < TT; ++t)
-            acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                a, __builtin_bit_cast(bf16x8_t, xb[t][s]), acc[t], 0, 0, 0);
-        }
-      }
-#pragma unroll
-      for (int t = 0; t < TT; ++t)
-#pragma unroll
-        for (int s = 0; s < 4; ++s) xb[t][s] = xn[t][s];
-    }
-#pragma unroll
-    for (int t = 0; t < TT; ++t)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) total[t][v] += acc[t][v];
+  const int nchunks = (d + kRouteKC - 1) / kRouteKC;
+  // One chunk: k blocks (BA, BB) against weight buffer BUF.
+#define MOGA_ROUTE_CHUNK(BA, BB, BUF, C)                                          \
+  {                                                                                \
+    const int k0 = (C) * kRouteKC;                                                 \
+    const bool more = (C) + 1 < nchunks;                                           \
+    if (more) route_load_w<NWV>(w, d, M, k0 + kRouteKC, wv);                         \
+    floatx16_t acc[TT];                                                            \
+    _Pragma("unroll") for (int t = 0; t < TT; ++t)                                 \
+      _Pragma("unroll") for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;              \
+    route_mfma_block<TT>(acc, s_w[BUF], 0, r, h, BA);                              \
+    route_load_x<TT>(BA, xrow, min(k0 + 256, last_kb));                            \
+    if (k0 + 64 < d) route_mfma_block<TT>(acc, s_w[BUF], 64, r, h, BB);            \
+    route_load_x<TT>(BB, xrow, min(k0 + 320, last_kb));                            \
+    _Pragma("unroll") for (int t = 0; t < TT; ++t)                                 \
+      _Pragma("unroll") for (int v = 0; v < 16; ++v) total[t][v] += acc[t][v];     \
+    if (more) route_store_w<NWV>(s_w[(BUF) ^ 1], wv);                                \
+    __syncthreads();                                                               \
   }
+  for (int c = 0; c < nchunks; c += 2) {
+    MOGA_ROUTE_CHUNK(b0, b1, 0, c)
+    if (c + 1 < nchunks) MOGA_ROUTE_CHUNK(b2, b3, 1, c + 1)
+  }
+#undef MOGA_ROUTE_CHUNK
 
   // Epilogue: accumulator register v of lane (r, h) is group row 8*(v/4) + 4*h + v%4 of token r.
+  const bool vec4 = (M & 3) == 0 && (((uintptr_t)probs | (uintptr_t)logits) & 15) == 0;
 #pragma unroll
   for (int t = 0; t < TT; ++t) {
     const int64_t tok = tok0 + 32 * t + r;
@@ -219,12 +266,29 @@ __global__ __launch_bounds__(256, 2) void route_mfma_kernel(
     const float g = 1.f / sum;
     if (tok < N) {
       if (h == 0) { group[tok] = bi; gate[tok] = g; }
+      if (vec4) {   // a lane's registers 4q .. 4q+3 are four consecutive groups: one 16-byte store
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int row = 8 * (v >> 2) + 4 * h + (v & 3);
-        if (row < M) {
-          if (probs) probs[tok * M + row] = e[v] * g;
-          if (logits) logits[tok * M + row] = vals[v];
+        for (int q = 0; q < 4; ++q) {
+          const int row = 8 * q + 4 * h;
+          if (row < M) {
+            if (probs) {
+              const floatx4_t pv = {e[4 * q] * g, e[4 * q + 1] * g, e[4 * q + 2] * g, e[4 * q + 3] * g};
+              *(floatx4_t*)(probs + tok * M + row) = pv;
+            }
+            if (logits) {
+              const floatx4_t lv = {vals[4 * q], vals[4 * q + 1], vals[4 * q + 2], vals[4 * q + 3]};
+              *(floatx4_t*)(logits + tok * M + row) = lv;
+            }
+          }
+        }
+      } else {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = 8 * (v >> 2) + 4 * h + (v & 3);
+          if (row < M) {
+            if (probs) probs[tok * M + row] = e[v] * g;
+            if (logits) logits[tok * M + row] = vals[v];
+          }
         }
       }
     }
@@ -537,12 +601,12 @@ extern "C" int moga_route(const void* x, int x_dtype, const float* w, const floa
   if (x_dtype == MOGA_BF16 && M <= 32 && d_model % 64 == 0) {
     if (N >= 65536) {
       const unsigned blocks = (unsigned)((N + 255) / 256);
-      route_mfma_kernel<2><<<blocks, 256, 0, st>>>((const unsigned short*)x, w, bias, N, d_model, M,
-                                                  group, gate, probs, logits);
+      route_mfma_kernel<2, 4><<<blocks, 256, 0, st>>>((const unsigned short*)x, w, bias, N, d_model, M,
+                                                     group, gate, probs, logits);
     } else {
       const unsigned blocks = (unsigned)((N + 127) / 128);
-      route_mfma_kernel<1><<<blocks, 256, 0, st>>>((const unsigned short*)x, w, bias, N, d_model, M,
-                                                  group, gate, probs, logits);
+      route_mfma_kernel<1, 4><<<blocks, 256, 0, st>>>((const unsigned short*)x, w, bias, N, d_model, M,
+                                                     group, gate, probs, logits);
     }
   } else {
     const unsigned blocks = (unsigned)((N + 3) / 4);
