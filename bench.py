@@ -31,9 +31,9 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, published
 # by what the same counter reads for a plain 1 GiB copy: FETCH x 2.00, WRITE x 1.00).  Summary and
 # commands: profiles/layer_C4b_hbm_traffic.md.  Only the workload it was measured on has an entry.
 MEASURED_HBM_BYTES = {
-    ("C4b", "moga_route"): 6.10e9, ("C4b", "moga_permute"): 35.7e9, ("C4b", "moga_group_attn_fwd"): 68.8e9,
+    ("C4b", "moga_route"): 6.11e9, ("C4b", "moga_permute"): 35.7e9, ("C4b", "moga_group_attn_fwd"): 68.7e9,
     ("C4b", "moga_unpermute"): 11.9e9, ("C4b", "moga_unpermute_bwd"): 17.9e9,
-    ("C4b", "moga_group_attn_bwd"): 220.0e9, ("C4b", "moga_permute_bwd"): 35.7e9, ("C4b", "moga_route_bwd"): 6.52e9,
+    ("C4b", "moga_group_attn_bwd"): 220.3e9, ("C4b", "moga_permute_bwd"): 35.7e9, ("C4b", "moga_route_bwd"): 6.53e9,
 }
 
 
