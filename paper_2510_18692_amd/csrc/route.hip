@@ -175,7 +175,7 @@ __device__ __forceinline__ void route_mfma_block(floatx16_t (&acc)[TT],
 // is unrolled over two chunks, so no set is ever copied): a set is refilled, four k blocks ahead,
 // right after its MFMAs, which keeps 16-32 KB of loads per wave in flight across the barriers.
 template <int TT, int NWV>  // 32-token tiles per wave, waves per block
-__global__ __launch_bounds__(64 * NWV, 8 / NWV) void route_mfma_kernel(
+__global__ __launch_bounds__(64 * NWV, 2) void route_mfma_kernel(
     const unsigned short* __restrict__ x, const float* __restrict__ w,
     const float* __restrict__ bias, int64_t N, int d, int M, int32_t* __restrict__ group,
     float* __restrict__ gate, float* __restrict__ probs, float* __restrict__ logits) {
