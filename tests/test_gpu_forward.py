@@ -34,6 +34,8 @@ def say(*a):
     (130, 64, 32, "bf16", False),      # MFMA path, one k block, full 32 rows
     (70000, 320, 20, "bf16", False),   # MFMA path with two token tiles per wave, ragged tail
     (1, 64, 1, "bf16", False),         # single token, single group
+    (300, 192, 12, "bf16", True),      # MFMA path, three k blocks: the second weight chunk is half full
+    (515, 128, 32, "bf16", False),     # MFMA path, exactly one weight chunk
 ])
 def test_route_matches_oracle(N, d, M, dtype, bias):
     say(f"route N={N} d={d} M={M} {dtype} bias={bias}")
