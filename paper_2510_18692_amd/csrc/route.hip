@@ -396,6 +396,64 @@ __global__ __launch_bounds__(256) void route_bwd_dx_kernel(
   }
 }
 
+// dX for M <= 32 and d a multiple of 4: a thread owns four adjacent columns and keeps their 32
+// weights in registers; a block sweeps kDxTokens tokens in tiles of kRbTok, whose dr rows are staged
+// in LDS and read back as broadcast 16-byte pieces (8 LDS reads for 128 FMAs per token).  Every
+// output row leaves as 16-byte stores, 1 KB contiguous per wave.  Sums run over the groups in
+// ascending order: exact fp32 FMA chains, the same for every launch.
+constexpr int kDxTokens = 512;   // tokens per block
+
+__global__ __launch_bounds__(256) void route_bwd_dx_cols_kernel(
+    const float* __restrict__ w, const float* __restrict__ probs,
+    const int32_t* __restrict__ group, const float* __restrict__ gate,
+    const float* __restrict__ d_gate, int64_t N, int d, int M, float* __restrict__ d_x) {
+  __shared__ __attribute__((aligned(16))) float s_dr[kRbTok][32];
+  const int c0 = (blockIdx.y * 256 + threadIdx.x) * 4;
+  const bool valid = c0 < d;
+  floatx4_t wreg[32];
+#pragma unroll
+  for (int j = 0; j < 32; ++j) {
+    const floatx4_t z = {0.f, 0.f, 0.f, 0.f};
+    wreg[j] = (valid && j < M) ? *(const floatx4_t*)(w + (int64_t)j * d + c0) : z;
+  }
+  const int64_t t_begin = (int64_t)blockIdx.x * kDxTokens;
+  const int64_t t_end = min(N, t_begin + kDxTokens);
+  for (int64_t tb = t_begin; tb < t_end; tb += kRbTok) {
+    const int nt = (int)min((int64_t)kRbTok, t_end - tb);
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < kRbTok * 32; idx += 256) {
+      const int ti = idx >> 5, j = idx & 31;
+      float v = 0.f;
+      if (ti < nt && j < M) {
+        const int64_t tok = tb + ti;
+        const float coef = d_gate[tok] * gate[tok];
+        const float onehot = (group[tok] == j) ? 1.f : 0.f;
+        v = coef * (onehot - probs[tok * M + j]);
+      }
+      s_dr[ti][j] = v;
+    }
+    __syncthreads();
+    if (valid) {
+      for (int ti = 0; ti < nt; ++ti) {
+        floatx4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j4 = 0; j4 < 8; ++j4) {
+          const floatx4_t r = *(const floatx4_t*)&s_dr[ti][4 * j4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const floatx4_t wv = wreg[4 * j4 + e];
+            acc[0] = fmaf(r[e], wv[0], acc[0]);
+            acc[1] = fmaf(r[e], wv[1], acc[1]);
+            acc[2] = fmaf(r[e], wv[2], acc[2]);
+            acc[3] = fmaf(r[e], wv[3], acc[3]);
+          }
+        }
+        *(floatx4_t*)(d_x + (tb + ti) * (int64_t)d + c0) = acc;
+      }
+    }
+  }
+}
+
 // ---------------------------------------------------------------------------------------
 // dW on the matrix cores (bf16 X, M <= 32, d a multiple of 256).
 //
@@ -667,8 +725,13 @@ extern "C" int moga_route_bwd(const void* x, int x_dtype, const float* w, const 
     route_bwd_dw_reduce_kernel<<<(unsigned)((md + 255) / 256), 256, 0, st>>>(partial, splits, md, d_w);
   }
   if (d_x) {
-    dim3 gx((unsigned)((N + kRbTok - 1) / kRbTok), (d_model + 255) / 256);
-    route_bwd_dx_kernel<<<gx, 256, 0, st>>>(w, probs, group, gate, d_gate, N, d_model, M, d_x);
+    if (M <= 32 && d_model % 4 == 0 && aligned16(d_x) && aligned16(w)) {
+      dim3 gx((unsigned)((N + kDxTokens - 1) / kDxTokens), (d_model + 1023) / 1024);
+      route_bwd_dx_cols_kernel<<<gx, 256, 0, st>>>(w, probs, group, gate, d_gate, N, d_model, M, d_x);
+    } else {
+      dim3 gx((unsigned)((N + kRbTok - 1) / kRbTok), (d_model + 255) / 256);
+      route_bwd_dx_kernel<<<gx, 256, 0, st>>>(w, probs, group, gate, d_gate, N, d_model, M, d_x);
+    }
   }
   return launch_status();
 }

@@ -106,7 +106,8 @@ def test_group_attention_backward_matches_oracle(sizes, H, D, dtype):
 @pytest.mark.parametrize("N,d,M,dtype,want_dx", [(4096, 128, 8, "f32", True), (5000, 1536, 8, "bf16", False),
                                                  (777, 200, 40, "bf16", True), (130000, 64, 5, "bf16", False),
                                                  (3001, 512, 32, "bf16", True), (17, 256, 1, "bf16", False),
-                                                 (1, 256, 3, "bf16", False), (70000, 2560, 16, "bf16", False)])
+                                                 (1, 256, 3, "bf16", False), (70000, 2560, 16, "bf16", False),
+                                                 (1500, 1028, 32, "bf16", True), (600, 1000, 5, "f32", True)])
 def test_route_bwd_matches_oracle(N, d, M, dtype, want_dx):
     say(f"route_bwd N={N} d={d} M={M} {dtype}")
     g = torch.Generator().manual_seed(N + d)
