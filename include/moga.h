@@ -257,6 +257,23 @@ int moga_gather_rows_bwd(const void* d_dst, int dtype, const int32_t* inv_cu, co
                          int64_t N, int64_t Nk, int H, int D, int accumulate, void* d_src, void* stream);
 
 /*
+ * Gradient of a token-order tensor (Q, K or V) that fed all three branches of Section 3.2, in one
+ * pass:  d_src[t][h][:] = g_moga[h][inv_moga[t]][:]
+ *                         + sum of g_stga[h][j][:] over the slots j that list token t
+ *                         + g_frame[h][inv_frame[t]][:]
+ * g_moga, g_frame [H, N, D]; g_stga [H, Nk, D]; inv_moga [N] (the inv_perm of moga_permute);
+ * inv_cu [N+1], inv_slots [Nk] as for moga_gather_rows_bwd (for the queries, which are listed
+ * once: inv_cu = 0..N and inv_slots = q_slot); inv_frame [N] or NULL for the identity.  One fp32
+ * sum per element in the order written above (slots ascending), rounded once; d_src [N, H, D] is
+ * overwritten.  Equivalent to moga_permute_bwd followed by two accumulating
+ * moga_gather_rows_bwd calls, with half the memory traffic and one rounding instead of three.
+ */
+int moga_gather3_bwd(const void* g_moga, const int32_t* inv_moga, const void* g_stga,
+                     const int32_t* inv_cu, const int32_t* inv_slots, int64_t Nk,
+                     const void* g_frame, const int32_t* inv_frame, int dtype, int64_t N, int H,
+                     int D, void* d_src, void* stream);
+
+/*
  * Mean of the three branches of Section 3.2 fused into one scatter:
  *   o[t][h][:] = ( gate[t] * a_moga[h][inv_moga[t]][:] + a_stga[h][inv_stga[t]][:]
  *                  + a_frame[h][inv_frame[t]][:] ) / 3

@@ -50,6 +50,7 @@ _SIGNATURES = {
                                      _vp, _vp]),
     "moga_gather_rows": (_i32, [_vp, _i32, _vp, _i64, _i32, _i32, _vp, _vp]),
     "moga_gather_rows_bwd": (_i32, [_vp, _i32, _vp, _vp, _i64, _i64, _i32, _i32, _i32, _vp, _vp]),
+    "moga_gather3_bwd": (_i32, [_vp, _vp, _vp, _vp, _vp, _i64, _vp, _vp, _i32, _i64, _i32, _i32, _vp, _vp]),
     "moga_merge3_fwd": (_i32, [_vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _vp]),
     "moga_merge3_bwd": (_i32, [_vp, _vp, _i32, _vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp, _vp]),
     "moga_balance_loss": (_i32, [_vp, _vp, _i64, _i32, _f32, _vp, _vp, _vp, _vp, _sz, _vp]),
@@ -334,6 +335,17 @@ def moga_gather_rows_bwd(d_dst, inv_cu, inv_slots, N, d_src=None, stream=None):
     return d_src
 
 
+def moga_gather3_bwd(g_moga, inv_moga, g_stga, inv_cu, inv_slots, g_frame, inv_frame=None, stream=None):
+    """g_moga, g_frame [H, N, D], g_stga [H, Nk, D] -> their token-order sum [N, H, D] (one pass)."""
+    H, N, D = g_moga.shape
+    Nk = g_stga.shape[1]
+    d_src = torch.empty((N, H, D), dtype=g_moga.dtype, device=g_moga.device)
+    st = load().moga_gather3_bwd(_p(g_moga), _p(inv_moga), _p(g_stga), _p(inv_cu), _p(inv_slots), Nk,
+                                 _p(g_frame), _p(inv_frame), _dt(g_moga), N, H, D, _p(d_src), _stream(stream))
+    _check("moga_gather3_bwd", st)
+    return d_src
+
+
 def moga_merge3_fwd(a_moga, a_stga, a_frame, inv_moga, inv_stga, inv_frame, gate, stream=None):
     """Three [H, N, D] branch outputs -> their mean [N, H, D] in token order (dynamic branch gated)."""
     H, N, D = a_moga.shape
@@ -433,22 +445,22 @@ def visual_forward(x, w, q, k, v, softmax_scale, grid, static_index, stream=None
 def visual_backward(fwd, x, w, d_o, softmax_scale, stream=None):
     """Backward of `visual_forward` -> dict(d_q, d_k, d_v [N, H, D], d_w [M, d_model], d_gate [N])."""
     pm, si, ident = fwd["pm"], fwd["si"], fwd["ident"]
-    N = d_o.shape[0]
     d_m, d_s, d_f, d_gate = moga_merge3_bwd(d_o, fwd["a_m"], pm["inv_perm"], si["q_slot"], None, fwd["gate"],
                                             stream=stream)
     dqm, dkm, dvm = moga_group_attn_bwd(d_m, pm["qh"], pm["kh"], pm["vh"], fwd["a_m"], fwd["lse_m"],
                                         pm["cu_seqlens"], softmax_scale, stream=stream)
-    d_q, d_k, d_v = moga_permute_bwd(dqm, dkm, dvm, pm["perm"], stream=stream)
-    del dqm, dkm, dvm, d_m
+    del d_m
     dqs, dks, dvs = moga_varlen_attn_bwd(d_s, fwd["qs"], fwd["ks"], fwd["vs"], fwd["a_s"], fwd["lse_s"],
                                          si["cu_q"], si["cu_k"], softmax_scale, stream=stream)
-    moga_gather_rows_bwd(dqs, ident, si["q_slot"], N, d_src=d_q, stream=stream)
-    moga_gather_rows_bwd(dks, si["inv_cu"], si["inv_slots"], N, d_src=d_k, stream=stream)
-    moga_gather_rows_bwd(dvs, si["inv_cu"], si["inv_slots"], N, d_src=d_v, stream=stream)
-    del dqs, dks, dvs, d_s
+    del d_s
     dqf, dkf, dvf = moga_varlen_attn_bwd(d_f, fwd["qf"], fwd["kf"], fwd["vf"], fwd["a_f"], fwd["lse_f"],
                                          fwd["cu_f"], fwd["cu_f"], softmax_scale, stream=stream)
-    for dst, src in ((d_q, dqf), (d_k, dkf), (d_v, dvf)):
-        moga_gather_rows_bwd(src, ident, ident[:N], N, d_src=dst, stream=stream)
+    del d_f
+    # every token-order gradient is written once: MoGA rows through inv_perm, the static rows through
+    # their slot lists (queries are listed once, keys possibly several times), the frame rows in place
+    d_q = moga_gather3_bwd(dqm, pm["inv_perm"], dqs, ident, si["q_slot"], dqf, stream=stream)
+    d_k = moga_gather3_bwd(dkm, pm["inv_perm"], dks, si["inv_cu"], si["inv_slots"], dkf, stream=stream)
+    d_v = moga_gather3_bwd(dvm, pm["inv_perm"], dvs, si["inv_cu"], si["inv_slots"], dvf, stream=stream)
+    del dqm, dkm, dvm, dqs, dks, dvs, dqf, dkf, dvf
     d_w, _ = moga_route_bwd(x, w, fwd["probs"], fwd["group"], fwd["gate"], d_gate, stream=stream)
     return {"d_q": d_q, "d_k": d_k, "d_v": d_v, "d_w": d_w, "d_gate": d_gate}

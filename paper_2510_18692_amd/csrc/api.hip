@@ -19,7 +19,7 @@ extern "C" const char* moga_status_string(int status) {
   }
 }
 
-extern "C" int moga_version(void) { return 102; }
+extern "C" int moga_version(void) { return 103; }
 
 extern "C" size_t moga_workspace_bytes(int op, int64_t N, int H, int D, int M, int d_model,
                                        int dtype) {

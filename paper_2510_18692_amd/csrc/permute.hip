@@ -371,6 +371,55 @@ __global__ __launch_bounds__(256) void gather_rows_bwd_kernel(
   }
 }
 
+// Gradient of a token-order tensor that fed all three branches (Q, K or V of Section 3.2's block):
+//   d_src[t][h] = g_m[h][inv_m[t]] + sum over the slots j of t of g_s[h][j] + g_f[h][inv_f[t]]
+// (inv_f NULL = identity).  One fp32 sum per element in this fixed order, rounded once: a single
+// pass instead of a scatter followed by two accumulating gather-backwards.
+template <int LPR, bool BF16>
+__global__ __launch_bounds__(256) void gather3_bwd_kernel(
+    const uintx4_t* __restrict__ g_m, const int32_t* __restrict__ inv_m,
+    const uintx4_t* __restrict__ g_s, const int32_t* __restrict__ inv_cu,
+    const int32_t* __restrict__ inv_slots, int64_t Nk, const uintx4_t* __restrict__ g_f,
+    const int32_t* __restrict__ inv_f, int64_t N, int H, uintx4_t* __restrict__ d_src) {
+  constexpr int RPW = 64 / LPR;
+  constexpr int IT = kSlotsPerBlock / RPW;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int part = lane % LPR, rsub = lane / LPR;
+  const int64_t t0 = (int64_t)blockIdx.x * kSlotsPerBlock;
+  int64_t jm[IT], jf[IT];
+  int beg[IT], end[IT];
+  bool ok[IT];
+#pragma unroll
+  for (int it = 0; it < IT; ++it) {
+    const int64_t t = t0 + it * RPW + rsub;
+    ok[it] = t < N;
+    jm[it] = ok[it] ? inv_m[t] : 0;
+    jf[it] = ok[it] ? (inv_f ? inv_f[t] : t) : 0;
+    beg[it] = ok[it] ? inv_cu[t] : 0;
+    end[it] = ok[it] ? inv_cu[t + 1] : 0;
+  }
+  for (int h = wave; h < H; h += 4) {
+    uintx4_t vm[IT], vf[IT];
+#pragma unroll
+    for (int it = 0; it < IT; ++it)
+      if (ok[it]) {
+        vm[it] = g_m[((int64_t)h * N + jm[it]) * LPR + part];
+        vf[it] = g_f[((int64_t)h * N + jf[it]) * LPR + part];
+      }
+#pragma unroll
+    for (int it = 0; it < IT; ++it)
+      if (ok[it]) {
+        const int64_t t = t0 + it * RPW + rsub;
+        float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        add16<BF16>(acc, vm[it]);
+        for (int j = beg[it]; j < end[it]; ++j)
+          add16<BF16>(acc, g_s[((int64_t)h * Nk + inv_slots[j]) * LPR + part]);
+        add16<BF16>(acc, vf[it]);
+        d_src[(t * H + h) * LPR + part] = pack16<BF16>(acc);
+      }
+  }
+}
+
 // o[t][h] = alpha * (gate[t] * a_m[h][inv_m[t]] + a_s[h][inv_s[t]] + a_f[h][inv_f[t]]); a NULL
 // inverse list means the identity (the branch keeps token order).
 template <int LPR, bool BF16>
@@ -676,6 +725,33 @@ extern "C" int moga_gather_rows_bwd(const void* d_dst, int dtype, const int32_t*
   else
     gather_rows_bwd_kernel<32, false><<<blocks, 256, 0, st>>>((const uintx4_t*)d_dst, inv_cu, inv_slots, N, Nk, H,
                                                               accumulate, (uintx4_t*)d_src);
+  return launch_status();
+}
+
+extern "C" int moga_gather3_bwd(const void* g_moga, const int32_t* inv_moga, const void* g_stga,
+                                const int32_t* inv_cu, const int32_t* inv_slots, int64_t Nk,
+                                const void* g_frame, const int32_t* inv_frame, int dtype, int64_t N,
+                                int H, int D, void* d_src, void* stream) {
+  const int bad = check_rows_args(dtype, N, H, D);
+  if (bad) return bad;
+  if (Nk < 0 || Nk >= ((int64_t)1 << 31)) return MOGA_ERR_INVALID_ARG;
+  if (N == 0) return MOGA_OK;
+  if (!g_moga || !inv_moga || !inv_cu || !g_frame || !d_src || (Nk > 0 && (!g_stga || !inv_slots)))
+    return MOGA_ERR_INVALID_ARG;
+  if (!(aligned16(g_moga) && aligned16(g_stga) && aligned16(g_frame) && aligned16(d_src)))
+    return MOGA_ERR_INVALID_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  const unsigned blocks = (unsigned)((N + kSlotsPerBlock - 1) / kSlotsPerBlock);
+  const int lpr = lanes_per_row(dtype, D);
+#define MOGA_GATHER3(LPR, BF)                                                                         \
+  gather3_bwd_kernel<LPR, BF><<<blocks, 256, 0, st>>>((const uintx4_t*)g_moga, inv_moga,              \
+                                                      (const uintx4_t*)g_stga, inv_cu, inv_slots, Nk, \
+                                                      (const uintx4_t*)g_frame, inv_frame, N, H,      \
+                                                      (uintx4_t*)d_src)
+  if (dtype == MOGA_BF16) MOGA_GATHER3(16, true);
+  else if (lpr == 16) MOGA_GATHER3(16, false);
+  else MOGA_GATHER3(32, false);
+#undef MOGA_GATHER3
   return launch_status();
 }
 

@@ -118,6 +118,9 @@ def test_new_entry_points_validate_arguments_without_a_gpu():
     assert lib.moga_gather_rows(fake, 1, fake, 10, 2, 100, fake, None) == -2
     assert lib.moga_gather_rows_bwd(fake, 1, None, fake, 10, 12, 2, 128, 0, fake, None) == -1
     assert lib.moga_merge3_fwd(fake, fake, None, 1, None, None, None, fake, 10, 2, 128, fake, None) == -1
+    assert lib.moga_gather3_bwd(fake, None, fake, fake, fake, 12, fake, None, 1, 10, 2, 128, fake, None) == -1
+    assert lib.moga_gather3_bwd(fake, fake, fake, fake, fake, 12, fake, None, 1, 10, 2, 100, fake, None) == -2
+    assert lib.moga_gather3_bwd(None, None, None, None, None, 0, None, None, 1, 0, 2, 128, None, None) == 0
     assert lib.moga_merge3_bwd(fake, fake, 1, None, None, None, fake, 10, 2, 128, fake, fake, fake, None, None) == -1
     wb = binding.workspace_bytes
     assert wb(binding.OP_VARLEN_ATTN_FWD, 1000, 2, 128, 500, 0, 1) >= 501 * 4

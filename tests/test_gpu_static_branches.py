@@ -46,6 +46,39 @@ def test_gather_with_repeats_and_its_backward(dtype, D):
     np.testing.assert_allclose(P.to64(acc), P.to64(base) + ref, rtol=tol["rtol"], atol=2e-2 if dtype == "bf16" else 1e-5)
 
 
+@pytest.mark.parametrize("dtype,D", [("bf16", 128), ("f32", 64), ("f32", 128)])
+def test_one_pass_sum_of_the_three_branch_gradients(dtype, D):
+    """moga_gather3_bwd against the sum written out on the host, and against the three calls it replaces."""
+    N, H, Nk = 1003, 3, 1400
+    g = torch.Generator().manual_seed(5 + D)
+    g_m, g_f = (torch.randn((H, N, D), generator=g).to(tdt(dtype)) for _ in range(2))
+    g_s = torch.randn((H, Nk, D), generator=g).to(tdt(dtype))
+    perm = torch.randperm(N, generator=g).to(torch.int32)
+    inv_m = torch.empty_like(perm)
+    inv_m[perm.long()] = torch.arange(N, dtype=torch.int32)
+    index = torch.randint(0, N, (Nk,), generator=g, dtype=torch.int32)      # token listed by slot j
+    index[:4] = 9                                                          # a token with several slots
+    index[index == 11] = 12                                                # a token with none
+    order = np.argsort(index.numpy(), kind="stable").astype(np.int32)
+    counts = np.bincount(index.numpy(), minlength=N)
+    inv_cu = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    tok = lambda a: np.transpose(P.to64(a), (1, 0, 2))
+    ref = tok(g_m)[inv_m.numpy()] + tok(g_f)
+    np.add.at(ref, index.numpy().astype(np.int64), tok(g_s))
+    cu, sl = torch.from_numpy(inv_cu).cuda(), torch.from_numpy(order).cuda()
+    got = mg.moga_gather3_bwd(g_m.cuda(), inv_m.cuda(), g_s.cuda(), cu, sl, g_f.cuda())
+    torch.cuda.synchronize()
+    tol = dict(rtol=1e-6, atol=1e-6) if dtype == "f32" else dict(rtol=2 ** -8, atol=1e-6)   # one rounding
+    np.testing.assert_allclose(P.to64(got), ref, **tol)
+    # the calls it replaces round after every step (bf16): same result within those roundings
+    d, _, _ = mg.moga_permute_bwd(g_m.cuda(), g_m.cuda(), g_m.cuda(), perm.cuda())
+    mg.moga_gather_rows_bwd(g_s.cuda(), cu, sl, N, d_src=d)
+    ident = torch.arange(N + 1, dtype=torch.int32).cuda()
+    mg.moga_gather_rows_bwd(g_f.cuda(), ident, ident[:N], N, d_src=d)
+    np.testing.assert_allclose(P.to64(d), P.to64(got), rtol=2 ** -6 if dtype == "bf16" else 1e-5,
+                               atol=3e-2 if dtype == "bf16" else 1e-5)
+
+
 @pytest.mark.parametrize("dtype,D", [("bf16", 128), ("f32", 64)])
 def test_merge_of_three_branches_and_its_backward(dtype, D):
     N, H = 1000, 5
