@@ -101,6 +101,24 @@ int moga_permute(const int32_t* group, int64_t N, int M,
                  void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * moga_permute for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments
+ * (minus ws), same kernels and bit-identical outputs; the per-chunk histograms live in a static
+ * device array of MOGA_PERMUTE_STATIC_MAX_BYTES that each GPU the library runs on holds until
+ * the process ends.  The call allocates nothing.  Sizes whose chunk histograms
+ * (moga_workspace_bytes(MOGA_OP_PERMUTE, N, .., M, ..)) exceed that limit return
+ * MOGA_ERR_UNSUPPORTED: with at most 8192 chunks, every N < 2^31 fits for M <= 64.  All calls
+ * on one GPU share the array: calls that overlap on one GPU (two streams, two threads) race;
+ * calls in stream order on one stream do not.
+ */
+#define MOGA_PERMUTE_STATIC_MAX_BYTES (2u << 20)
+int moga_permute_static(const int32_t* group, int64_t N, int M,
+                        const void* q, const void* k, const void* v, int dtype, int H, int D,
+                        int32_t* counts, int32_t* cu_seqlens, int32_t* max_seqlen,
+                        int32_t* perm, int32_t* inv_perm,
+                        void* qh, void* kh, void* vh, void* stream);
+
+/*
  * Variable-length attention of Alg. 1 step 3: Eq. 1 applied independently inside each
  * group and head, bidirectional:
  *   oh[h][j] = softmax_k(softmax_scale * qh[h][j] . kh[h][k]) vh[h][k],  k over j's group

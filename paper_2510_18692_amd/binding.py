@@ -29,6 +29,8 @@ _SIGNATURES = {
     "moga_route": (_i32, [_vp, _i32, _vp, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "moga_permute": (_i32, [_vp, _i64, _i32, _vp, _vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp,
                             _vp, _vp, _vp, _vp, _sz, _vp]),
+    "moga_permute_static": (_i32, [_vp, _i64, _i32, _vp, _vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp,
+                                   _vp, _vp, _vp, _vp, _vp]),
     "moga_group_attn_fwd": (_i32, [_vp, _vp, _vp, _i32, _i64, _i32, _i32, _vp, _i32, _f32, _vp, _vp,
                                    _vp, _sz, _vp]),
     "moga_unpermute": (_i32, [_vp, _i32, _vp, _vp, _i64, _i32, _i32, _vp, _vp]),
@@ -162,6 +164,24 @@ def moga_permute(group, M, q=None, k=None, v=None, stream=None):
                              _p(out["inv_perm"]), _p(out.get("qh")), _p(out.get("kh")),
                              _p(out.get("vh")), _p(ws), ws.numel(), _stream(stream))
     _check("moga_permute", st)
+    return out
+
+
+def moga_permute_static(group, M, out, q=None, k=None, v=None, stream=None):
+    """moga_permute without a workspace and without any allocation, here or in the library:
+    `out` holds the caller's tensors counts [M], cu_seqlens [M+1], max_seqlen [1], perm [N],
+    inv_perm [N] (and qh, kh, vh [H, N, D] when q, k, v are given); they are written in place."""
+    N = group.shape[0]
+    H = D = 0
+    dt = MOGA_F32
+    if q is not None:
+        _, H, D = q.shape
+        dt = _dt(q)
+    st = load().moga_permute_static(_p(group), N, M, _p(q), _p(k), _p(v), dt, H, D, _p(out["counts"]),
+                                    _p(out["cu_seqlens"]), _p(out["max_seqlen"]), _p(out["perm"]),
+                                    _p(out["inv_perm"]), _p(out.get("qh")), _p(out.get("kh")),
+                                    _p(out.get("vh")), _stream(stream))
+    _check("moga_permute_static", st)
     return out
 
 

@@ -9,6 +9,8 @@
 //                    running base for the group plus its rank among equal ids in the batch.
 // Data part: 16-byte-per-lane row copies between token order [N, H, D] and head-major
 // group-contiguous order [H, N, D]; the scatter back multiplies by the gate (Eq. 5).
+#include <mutex>
+
 #include "moga_common.h"
 
 namespace moga {
@@ -574,33 +576,16 @@ extern "C" size_t moga_permute_ws_bytes(int64_t N, int M) {
   return (size_t)perm_num_chunks(N) * (size_t)M * sizeof(int32_t);
 }
 
-extern "C" int moga_permute(const int32_t* group, int64_t N, int M, const void* q, const void* k,
-                            const void* v, int dtype, int H, int D, int32_t* counts,
-                            int32_t* cu_seqlens, int32_t* max_seqlen, int32_t* perm,
-                            int32_t* inv_perm, void* qh, void* kh, void* vh, void* ws,
-                            size_t ws_bytes, void* stream) {
-  if (N < 0 || M < 1) return MOGA_ERR_INVALID_ARG;
-  if (M > MOGA_MAX_GROUPS || N >= ((int64_t)1 << 31)) return MOGA_ERR_UNSUPPORTED;
+// Shared body of moga_permute and moga_permute_static: `hist` holds num_chunks * M int32.
+static int permute_impl(const int32_t* group, int64_t N, int M, const void* q, const void* k,
+                        const void* v, int dtype, int H, int D, int32_t* counts,
+                        int32_t* cu_seqlens, int32_t* max_seqlen, int32_t* perm,
+                        int32_t* inv_perm, void* qh, void* kh, void* vh, int32_t* hist,
+                        hipStream_t st) {
   const bool with_data = q || k || v;
-  if (with_data) {
-    const int rc = check_rows_args(dtype, N, H, D);
-    if (rc != MOGA_OK) return rc;
-  }
-  if (!counts || !cu_seqlens || !max_seqlen) return MOGA_ERR_INVALID_ARG;
-  hipStream_t st = (hipStream_t)stream;
-  if (N > 0) {
-    if (!group || !perm || !inv_perm) return MOGA_ERR_INVALID_ARG;
-    if (with_data && (!q || !k || !v || !qh || !kh || !vh)) return MOGA_ERR_INVALID_ARG;
-    if (with_data && !(aligned16(q) && aligned16(k) && aligned16(v) && aligned16(qh) &&
-                       aligned16(kh) && aligned16(vh)))
-      return MOGA_ERR_INVALID_ARG;
-  }
-  const size_t need = moga_permute_ws_bytes(N, M);
-  if (need > 0 && (!ws || ws_bytes < need)) return MOGA_ERR_WORKSPACE;
   const int chunk_len = perm_chunk_len(N);
   const int num_chunks = perm_num_chunks(N);
   const int nbits = bits_for(M);
-  int32_t* hist = (int32_t*)ws;
   if (num_chunks > 0)
     chunk_hist_kernel<<<(num_chunks + 3) / 4, 256, 0, st>>>(group, N, M, nbits, chunk_len,
                                                            num_chunks, hist);
@@ -619,6 +604,86 @@ extern "C" int moga_permute(const int32_t* group, int64_t N, int M, const void* 
     }
   }
   return launch_status();
+}
+
+// Host-side argument checks shared by the two permute entry points.
+static int permute_check(const int32_t* group, int64_t N, int M, const void* q, const void* k,
+                         const void* v, int dtype, int H, int D, const int32_t* counts,
+                         const int32_t* cu_seqlens, const int32_t* max_seqlen,
+                         const int32_t* perm, const int32_t* inv_perm, const void* qh,
+                         const void* kh, const void* vh) {
+  if (N < 0 || M < 1) return MOGA_ERR_INVALID_ARG;
+  if (M > MOGA_MAX_GROUPS || N >= ((int64_t)1 << 31)) return MOGA_ERR_UNSUPPORTED;
+  const bool with_data = q || k || v;
+  if (with_data) {
+    const int rc = check_rows_args(dtype, N, H, D);
+    if (rc != MOGA_OK) return rc;
+  }
+  if (!counts || !cu_seqlens || !max_seqlen) return MOGA_ERR_INVALID_ARG;
+  if (N > 0) {
+    if (!group || !perm || !inv_perm) return MOGA_ERR_INVALID_ARG;
+    if (with_data && (!q || !k || !v || !qh || !kh || !vh)) return MOGA_ERR_INVALID_ARG;
+    if (with_data && !(aligned16(q) && aligned16(k) && aligned16(v) && aligned16(qh) &&
+                       aligned16(kh) && aligned16(vh)))
+      return MOGA_ERR_INVALID_ARG;
+  }
+  return MOGA_OK;
+}
+
+extern "C" int moga_permute(const int32_t* group, int64_t N, int M, const void* q, const void* k,
+                            const void* v, int dtype, int H, int D, int32_t* counts,
+                            int32_t* cu_seqlens, int32_t* max_seqlen, int32_t* perm,
+                            int32_t* inv_perm, void* qh, void* kh, void* vh, void* ws,
+                            size_t ws_bytes, void* stream) {
+  const int rc = permute_check(group, N, M, q, k, v, dtype, H, D, counts, cu_seqlens, max_seqlen,
+                               perm, inv_perm, qh, kh, vh);
+  if (rc != MOGA_OK) return rc;
+  const size_t need = moga_permute_ws_bytes(N, M);
+  if (need > 0 && (!ws || ws_bytes < need)) return MOGA_ERR_WORKSPACE;
+  return permute_impl(group, N, M, q, k, v, dtype, H, D, counts, cu_seqlens, max_seqlen, perm,
+                      inv_perm, qh, kh, vh, (int32_t*)ws, (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------------------------------
+// moga_permute_static: the same call for callers that cannot allocate.  The per-chunk
+// histograms live in a file-scope device array; every GPU holds its own copy, whose address is
+// looked up once per device (the array's name is only a host-side handle, never a device
+// address).  chunk_hist overwrites every entry it later reads, so nothing has to be cleared
+// between calls; two calls that overlap on one GPU would share the array and race.
+// ---------------------------------------------------------------------------------------
+static __device__ __align__(256) int32_t scratch[MOGA_PERMUTE_STATIC_MAX_BYTES / sizeof(int32_t)];
+
+static constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static int32_t* g_scratch_ptr[kMaxDevices];  // per device, filled on the first call there
+
+// Device address of `scratch` on the current device, or nullptr when HIP reports an error.
+static int32_t* static_scratch_for_current_device() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+    g_scratch_ptr[dev] = (int32_t*)ptr;
+  }
+  return g_scratch_ptr[dev];
+}
+
+extern "C" int moga_permute_static(const int32_t* group, int64_t N, int M, const void* q,
+                                   const void* k, const void* v, int dtype, int H, int D,
+                                   int32_t* counts, int32_t* cu_seqlens, int32_t* max_seqlen,
+                                   int32_t* perm, int32_t* inv_perm, void* qh, void* kh,
+                                   void* vh, void* stream) {
+  const int rc = permute_check(group, N, M, q, k, v, dtype, H, D, counts, cu_seqlens, max_seqlen,
+                               perm, inv_perm, qh, kh, vh);
+  if (rc != MOGA_OK) return rc;
+  if (moga_permute_ws_bytes(N, M) > (size_t)MOGA_PERMUTE_STATIC_MAX_BYTES)
+    return MOGA_ERR_UNSUPPORTED;  // more chunk histograms than the static array holds
+  int32_t* hist = static_scratch_for_current_device();
+  if (!hist) return MOGA_ERR_HIP;
+  return permute_impl(group, N, M, q, k, v, dtype, H, D, counts, cu_seqlens, max_seqlen, perm,
+                      inv_perm, qh, kh, vh, hist, (hipStream_t)stream);
 }
 
 static int scatter_dispatch(const Rows3& p, int ntensors, int dtype, int D, const int32_t* perm,
