@@ -20,8 +20,9 @@
  *   - Notation: N tokens (batch 1), d_model router input width, M groups, H heads,
  *     D head_dim.  Token-order tensors are [N, H, D] row-major; group-contiguous
  *     ("hat") tensors are head-major [H, N, D], row j of a head being sorted slot j.
- *   - Supported: M in [1, 256]; N < 2^31; dtype F32 with D in {64, 128} and dtype BF16 with
- *     D = 128.  Anything else returns MOGA_ERR_UNSUPPORTED.
+ *   - Supported: M in [1, 256]; N < 2^31 (N < 2^24 for the BF16 attention calls, whose kernels
+ *     address the rows of a group with 32-bit byte offsets); dtype F32 with D in {64, 128} and
+ *     dtype BF16 with D = 128.  Anything else returns MOGA_ERR_UNSUPPORTED.
  */
 #ifndef MOGA_H_
 #define MOGA_H_
@@ -159,6 +160,19 @@ int moga_group_attn_bwd(const void* d_oh, const void* qh, const void* kh, const 
                         int64_t N, int H, int D, const int32_t* cu_seqlens, int M,
                         float softmax_scale, void* d_qh, void* d_kh, void* d_vh,
                         void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Diagnostics of the BF16 backward calls (moga_group_attn_bwd, moga_varlen_attn_bwd,
+ * moga_fused_attn_bwd).  Inside the dK/dV kernel one wave of a pair waits for values its partner
+ * publishes through LDS; the wait is bounded, and a wave that gives up sets an int32 status word in
+ * the workspace to a nonzero value and carries on, so the kernel always drains (the gradients of
+ * that call are then invalid).  The word lies at byte offset moga_attn_bwd_status_offset(Nq, H) of
+ * ws, is cleared by every call and is valid in stream order after it; it reads 0 after every
+ * correct run.  moga_debug_set_spin_limit sets the number of polls before a give-up (default 2^24;
+ * 0 makes every not-yet-satisfied wait give up at once: for tests of this path only).  Host-only.
+ */
+size_t moga_attn_bwd_status_offset(int64_t Nq, int H);
+void moga_debug_set_spin_limit(int polls);
 
 /* Backward of the gather in moga_permute: d_q[perm[j]][h][:] = d_qh[h][j][:] (same for k, v). */
 int moga_permute_bwd(const void* d_qh, const void* d_kh, const void* d_vh, int dtype,

@@ -37,6 +37,8 @@ _SIGNATURES = {
     "moga_unpermute_bwd": (_i32, [_vp, _vp, _i32, _vp, _vp, _i64, _i32, _i32, _vp, _vp, _vp]),
     "moga_group_attn_bwd": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _i64, _i32, _i32, _vp, _i32,
                                    _f32, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "moga_attn_bwd_status_offset": (_sz, [_i64, _i32]),
+    "moga_debug_set_spin_limit": (None, [_i32]),
     "moga_permute_bwd": (_i32, [_vp, _vp, _vp, _i32, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp]),
     "moga_route_bwd": (_i32, [_vp, _i32, _vp, _vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _vp, _vp,
                               _sz, _vp]),
@@ -217,12 +219,23 @@ def moga_unpermute_bwd(d_o, oh, perm, gate, stream=None):
     return d_oh, d_gate
 
 
-def moga_group_attn_bwd(d_oh, qh, kh, vh, oh, lse, cu_seqlens, softmax_scale, stream=None):
-    """-> (d_qh, d_kh, d_vh) each [H, N, D]"""
+def attn_bwd_status(ws, Nq, H):
+    """The int32 status word of a backward workspace (0 after every correct run), as a 1-element view."""
+    off = int(load().moga_attn_bwd_status_offset(Nq, H))
+    return ws[off:off + 4].view(torch.int32)
+
+
+def set_spin_limit(polls: int) -> None:
+    load().moga_debug_set_spin_limit(int(polls))
+
+
+def moga_group_attn_bwd(d_oh, qh, kh, vh, oh, lse, cu_seqlens, softmax_scale, stream=None, ws=None):
+    """-> (d_qh, d_kh, d_vh) each [H, N, D].  `ws`: the caller's workspace (uint8), else one is allocated."""
     H, N, D = qh.shape
     M = cu_seqlens.shape[0] - 1
     d_qh, d_kh, d_vh = torch.empty_like(qh), torch.empty_like(kh), torch.empty_like(vh)
-    ws = _ws(workspace_bytes(OP_ATTN_BWD, N, H, D, M, 0, _dt(qh)), qh.device)
+    if ws is None:
+        ws = _ws(workspace_bytes(OP_ATTN_BWD, N, H, D, M, 0, _dt(qh)), qh.device)
     st = load().moga_group_attn_bwd(_p(d_oh), _p(qh), _p(kh), _p(vh), _p(oh), _p(lse), _dt(qh), N, H, D,
                                     _p(cu_seqlens), M, float(softmax_scale), _p(d_qh), _p(d_kh),
                                     _p(d_vh), _p(ws), ws.numel(), _stream(stream))

@@ -12,6 +12,8 @@
 // product in the accumulator registers of the first (row permutation of the LDS operand), and
 // read the transposed operands (dO^T, Q^T, K^T) from row-major LDS tiles with the transposing
 // LDS read.  The fp32 kernels below use one thread per row.
+#include <atomic>
+
 #include "attn_common.h"
 #include "attn_bwd_pipe.h"
 
@@ -24,7 +26,9 @@ __global__ __launch_bounds__(256) void attn_bwd_delta_kernel(const uintx4_t* __r
                                                              const uintx4_t* __restrict__ oh,
                                                              const float* __restrict__ lse, int64_t rows,
                                                              float inv_scale, float* __restrict__ delta,
-                                                             float* __restrict__ neg_lse_over_scale) {
+                                                             float* __restrict__ neg_lse_over_scale,
+                                                             int* __restrict__ status) {
+  if (status && blockIdx.x == 0 && threadIdx.x == 0) *status = 0;   // read by the kernels that follow
   const int64_t row = ((int64_t)blockIdx.x * 256 + threadIdx.x) / LPR;
   const int part = threadIdx.x % LPR;
   float s = 0.f;
@@ -63,8 +67,9 @@ __global__ __launch_bounds__(256) void attn_bwd_fused_prepass_kernel(
     const uintx4_t* __restrict__ d_o, const uintx4_t* __restrict__ o, const float* __restrict__ lse,
     const int32_t* __restrict__ inv_perm, const float* __restrict__ gate, int64_t N, int H,
     float inv_scale, float* __restrict__ neg_lse_over_scale, float* __restrict__ neg_delta,
-    float* __restrict__ d_gate) {
+    float* __restrict__ d_gate, int* __restrict__ status) {
   __shared__ float s_part[4][16];
+  if (blockIdx.x == 0 && threadIdx.x == 0) *status = 0;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int part = lane & 15, rsub = lane >> 4;
   const int64_t t0 = (int64_t)blockIdx.x * 16;
@@ -250,11 +255,29 @@ __global__ __launch_bounds__(64) void attn_bwd_dkdv_f32_kernel(
 
 using namespace moga;
 
+// Workspace layout of the backward calls: [-delta: rows floats][-lse/scale: rows floats][status:
+// 16 bytes, first int32 used], rows = Nq * H; the varlen call appends its two tile-start lists.
+static size_t bwd_rows_bytes(int64_t Nq, int H) { return round_up(2 * (size_t)Nq * (size_t)H * sizeof(float), 16); }
+
+extern "C" size_t moga_attn_bwd_status_offset(int64_t Nq, int H) {
+  if (Nq <= 0 || H < 1) return 0;
+  return bwd_rows_bytes(Nq, H);
+}
+
 extern "C" size_t moga_attn_bwd_ws_bytes(int64_t N, int H, int D, int dtype) {
   (void)D; (void)dtype;
   if (N <= 0 || H < 1) return 0;
-  return 2 * (size_t)N * (size_t)H * sizeof(float);   // delta, lse * log2(e)
+  return bwd_rows_bytes(N, H) + 16;
 }
+
+// Polls after which a wave of the dK/dV kernel that waits for its partner's P gives up (and sets the
+// status word).  In normal operation a wait lasts a few hundred polls at most.
+static std::atomic<int> g_spin_limit{1 << 24};
+extern "C" void moga_debug_set_spin_limit(int polls) { g_spin_limit.store(polls < 0 ? 0 : polls); }
+
+// The bf16 kernels form per-lane byte offsets `row * 256` in 32 bits, relative to the first row of
+// a group: a group (hence a tensor) must have fewer than 2^24 rows.
+static bool bf16_rows_ok(int64_t Nq, int64_t Nk) { return Nq < ((int64_t)1 << 24) && Nk < ((int64_t)1 << 24); }
 
 // Shared launcher.  ts_q / ts_k: NULL (tile lookup inside the kernels, M <= MOGA_MAX_GROUPS) or
 // space for the pre-summed first-tile indices over query rows / key rows (M + 1 ints each).
@@ -264,26 +287,22 @@ static int launch_attn_bwd(const void* d_oh, const void* qh, const void* kh, con
                            int M, float softmax_scale, void* d_qh, void* d_kh, void* d_vh,
                            float* delta, hipStream_t st) {
   const int64_t rows = Nq * (int64_t)H;
+  if ((rows * 32 + 255) / 256 >= ((int64_t)1 << 31)) return MOGA_ERR_UNSUPPORTED;   // grid of the delta kernel
   if (dtype == MOGA_BF16) {
+    if (!bf16_rows_ok(Nq, Nk)) return MOGA_ERR_UNSUPPORTED;
     float* lse2 = delta + rows;   // holds -lse/scale; `delta` holds -delta
+    int* status = (int*)((char*)delta + bwd_rows_bytes(Nq, H));
     attn_bwd_delta_kernel<16, true><<<(unsigned)((rows * 16 + 255) / 256), 256, 0, st>>>(
-        (const uintx4_t*)d_oh, (const uintx4_t*)oh, lse, rows, 1.f / softmax_scale, delta, lse2);
+        (const uintx4_t*)d_oh, (const uintx4_t*)oh, lse, rows, 1.f / softmax_scale, delta, lse2, status);
     if (Nk > 0) {
       const int64_t tiles = max_tiles(Nk, M, 128);
       const int64_t blocks = (tiles * H + 7) / 8 * 8;
       if (blocks >= ((int64_t)1 << 31)) return MOGA_ERR_UNSUPPORTED;
       if (ts_k) tile_start_kernel<<<1, 1024, 0, st>>>(cu_k, M, 128, ts_k);
-#ifdef MOGA_DKDV_ONE_WAVE
-      attn_bwd_dkdv_pipe_kernel<4><<<(unsigned)blocks, 256, 0, st>>>(
-          (const unsigned short*)d_oh, (const unsigned short*)qh, (const unsigned short*)kh,
-          (const unsigned short*)vh, lse2, delta, cu_q, cu_k, ts_k, M, Nq, Nk, H, softmax_scale,
-          (int)tiles, (unsigned short*)d_kh, (unsigned short*)d_vh);
-#else
       attn_bwd_dkdv_ab_kernel<false><<<(unsigned)blocks, 512, 0, st>>>(
           (const unsigned short*)d_oh, (const unsigned short*)qh, (const unsigned short*)kh,
           (const unsigned short*)vh, lse2, delta, cu_q, cu_k, ts_k, M, Nq, Nk, H, softmax_scale,
-          (int)tiles, (unsigned short*)d_kh, (unsigned short*)d_vh);
-#endif
+          (int)tiles, (unsigned short*)d_kh, (unsigned short*)d_vh, g_spin_limit.load(), status);
     }
     {
       const int64_t tiles = max_tiles(Nq, M, 256);
@@ -298,10 +317,10 @@ static int launch_attn_bwd(const void* d_oh, const void* qh, const void* kh, con
   } else {
     if (D == 64)
       attn_bwd_delta_kernel<16, false><<<(unsigned)((rows * 16 + 255) / 256), 256, 0, st>>>(
-          (const uintx4_t*)d_oh, (const uintx4_t*)oh, lse, rows, 1.f, delta, nullptr);
+          (const uintx4_t*)d_oh, (const uintx4_t*)oh, lse, rows, 1.f, delta, nullptr, nullptr);
     else
       attn_bwd_delta_kernel<32, false><<<(unsigned)((rows * 32 + 255) / 256), 256, 0, st>>>(
-          (const uintx4_t*)d_oh, (const uintx4_t*)oh, lse, rows, 1.f, delta, nullptr);
+          (const uintx4_t*)d_oh, (const uintx4_t*)oh, lse, rows, 1.f, delta, nullptr, nullptr);
     if (Nk > 0) {
       const int64_t tiles = max_tiles(Nk, M, kF32BM);
       const int64_t blocks = tiles * H;
@@ -364,7 +383,7 @@ extern "C" int moga_group_attn_bwd(const void* d_oh, const void* qh, const void*
 
 extern "C" size_t moga_varlen_attn_bwd_ws_bytes(int64_t Nq, int H, int G) {
   if (Nq <= 0 || H < 1) return 0;
-  return round_up(2 * (size_t)Nq * (size_t)H * sizeof(float), 16) + 2 * ((size_t)G + 1) * sizeof(int32_t);
+  return bwd_rows_bytes(Nq, H) + 16 + 2 * ((size_t)G + 1) * sizeof(int32_t);
 }
 
 extern "C" int moga_varlen_attn_bwd(const void* d_oh, const void* qh, const void* kh, const void* vh,
@@ -392,7 +411,7 @@ extern "C" int moga_varlen_attn_bwd(const void* d_oh, const void* qh, const void
   }
   const size_t need = moga_varlen_attn_bwd_ws_bytes(Nq, H, G);
   if (!ws || ws_bytes < need || !aligned16(ws)) return MOGA_ERR_WORKSPACE;
-  int32_t* ts_q = (int32_t*)((char*)ws + round_up(2 * (size_t)Nq * (size_t)H * sizeof(float), 16));
+  int32_t* ts_q = (int32_t*)((char*)ws + bwd_rows_bytes(Nq, H) + 16);
   int32_t* ts_k = ts_q + (G + 1);
   return launch_attn_bwd(d_oh, qh, kh, vh, oh, lse, dtype, Nq, Nk, H, D, cu_seqlens_q, cu_seqlens_k, ts_q,
                          ts_k, G, softmax_scale, d_qh, d_kh, d_vh, (float*)ws, st);
@@ -406,7 +425,7 @@ extern "C" int moga_fused_attn_bwd(const void* d_o, const void* q, const void* k
                                    void* stream) {
   const int bad = check_attn_bwd_args(N, N, H, D, M, softmax_scale, dtype);
   if (bad) return bad;
-  if (M > MOGA_MAX_GROUPS || dtype != MOGA_BF16) return MOGA_ERR_UNSUPPORTED;
+  if (M > MOGA_MAX_GROUPS || dtype != MOGA_BF16 || !bf16_rows_ok(N, N)) return MOGA_ERR_UNSUPPORTED;
   if (N == 0) return MOGA_OK;
   if (!d_o || !q || !k || !v || !o || !lse || !perm || !inv_perm || !gate || !cu_seqlens || !d_q || !d_k ||
       !d_v || !d_gate)
@@ -419,8 +438,10 @@ extern "C" int moga_fused_attn_bwd(const void* d_o, const void* q, const void* k
   hipStream_t st = (hipStream_t)stream;
   float* delta = (float*)ws;
   float* lse2 = delta + N * (int64_t)H;
+  int* status = (int*)((char*)ws + bwd_rows_bytes(N, H));
   attn_bwd_fused_prepass_kernel<<<(unsigned)((N + 15) / 16), 256, 0, st>>>(
-      (const uintx4_t*)d_o, (const uintx4_t*)o, lse, inv_perm, gate, N, H, 1.f / softmax_scale, lse2, delta, d_gate);
+      (const uintx4_t*)d_o, (const uintx4_t*)o, lse, inv_perm, gate, N, H, 1.f / softmax_scale, lse2, delta, d_gate,
+      status);
   {
     const int64_t tiles = max_tiles(N, M, 128);
     const int64_t blocks = (tiles * H + 7) / 8 * 8;
@@ -428,11 +449,12 @@ extern "C" int moga_fused_attn_bwd(const void* d_o, const void* q, const void* k
     attn_bwd_dkdv_ab_kernel<true><<<(unsigned)blocks, 512, 0, st>>>(
         (const unsigned short*)d_o, (const unsigned short*)q, (const unsigned short*)k, (const unsigned short*)v,
         lse2, delta, cu_seqlens, cu_seqlens, nullptr, M, N, N, H, softmax_scale, (int)tiles, (unsigned short*)d_k,
-        (unsigned short*)d_v, perm);
+        (unsigned short*)d_v, g_spin_limit.load(), status, perm);
   }
   {
     const int64_t tiles = max_tiles(N, M, 256);
     const int64_t blocks = (tiles * H + 7) / 8 * 8;
+    if (blocks >= ((int64_t)1 << 31)) return MOGA_ERR_UNSUPPORTED;
     attn_bwd_dq_pipe_kernel<8, 1, true><<<(unsigned)blocks, 512, 0, st>>>(
         (const unsigned short*)d_o, (const unsigned short*)q, (const unsigned short*)k, (const unsigned short*)v,
         lse2, delta, cu_seqlens, cu_seqlens, nullptr, M, N, N, H, softmax_scale, (int)tiles, (unsigned short*)d_q,

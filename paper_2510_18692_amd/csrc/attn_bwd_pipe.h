@@ -5,10 +5,7 @@
 //                               K and V; three MFMA products per tile (S^T, dP^T, dQ^T).
 //   attn_bwd_dkdv_ab_kernel   : a pair of waves on one SIMD owns 32 key rows and sweeps 64-query
 //                               tiles of Q, dO, lse and delta; one wave computes S, P and dV^T,
-//                               the other dP, dS and dK^T (P handed over through LDS).  The one
-//                               the library launches.
-//   attn_bwd_dkdv_pipe_kernel : its predecessor: all four products (S, dP, dV^T, dK^T) in one
-//                               wave, one wave per SIMD (the accumulators need > 256 registers).
+//                               the other dP, dS and dK^T (P handed over through LDS).
 // Tiles are streamed global -> LDS by direct-to-LDS loads into a ring of four slots, two tiles
 // ahead; one block-wide barrier per tile.
 #pragma once
@@ -51,34 +48,6 @@ __device__ __forceinline__ void softmax_bwd_cols(const floatx16_t& s, const floa
       dd[j >> 1] = pack_bf16x2(pa * (dp[v] - dlt), pb * (dp[v + 1] - dlt));
     }
     const uintx4_t du = {dd[0], dd[1], dd[2], dd[3]};
-    dsf[kstep] = __builtin_bit_cast(bf16x8_t, du);
-  }
-}
-
-// dK/dV kernel: the score accumulators were started from -lse/scale and -delta of their rows, so
-// s already holds S - lse/scale and dp holds dP - delta: P = exp2(c*s), dS = P * dp.
-// `limit`: query rows >= limit (relative to the step's first) get P = 0 (MASK only).
-template <bool MASK>
-__device__ __forceinline__ void softmax_bwd_rows(const floatx16_t& s, const floatx16_t& dp, float c, int h,
-                                                 int limit, bf16x8_t (&pf)[2], bf16x8_t (&dsf)[2]) {
-#pragma unroll
-  for (int kstep = 0; kstep < 2; ++kstep) {
-    unsigned int pp[4], dd[4];
-#pragma unroll
-    for (int j = 0; j < 8; j += 2) {
-      const int v = 8 * kstep + j;
-      float pa = fast_exp2(s[v] * c);
-      float pb = fast_exp2(s[v + 1] * c);
-      if (MASK) {
-        const int idx = 16 * kstep + 8 * h + j;
-        if (idx >= limit) pa = 0.f;
-        if (idx + 1 >= limit) pb = 0.f;
-      }
-      pp[j >> 1] = pack_bf16x2(pa, pb);
-      dd[j >> 1] = pack_bf16x2(pa * dp[v], pb * dp[v + 1]);
-    }
-    const uintx4_t pu = {pp[0], pp[1], pp[2], pp[3]}, du = {dd[0], dd[1], dd[2], dd[3]};
-    pf[kstep] = __builtin_bit_cast(bf16x8_t, pu);
     dsf[kstep] = __builtin_bit_cast(bf16x8_t, du);
   }
 }
@@ -321,273 +290,6 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_pipe_kernel(
 }
 
 // ---------------------------------------------------------------------------------------
-// dK, dV: key-stationary
-// ---------------------------------------------------------------------------------------
-struct DkvLane {
-  unsigned q_nat[8], do_nat[8];     // Q / dO fragment (row = permuted lane row), slot 0, half 0
-  unsigned q_tr[4][2], do_tr[4][2]; // transposed Q / dO read for d tile dt, rows +0 / +4
-  unsigned lse_addr, delta_addr;    // -lse/scale and -delta of the lane's first row (8*h), slot 0, half 0
-};
-
-struct DkvFrags {
-  bf16x8_t qn[8], dn[8];   // Q, dO rows (A operands of S and dP)
-};
-struct DkvTrFrags {
-  bf16x8_t qtr[2][4], dtr[2][4];   // Q^T, dO^T (A operands of dK^T and dV^T)
-};
-
-template <int SOFF>
-__device__ __forceinline__ void dkdv_load_nat(const DkvLane& ln, unsigned off, DkvFrags& f) {
-#pragma unroll
-  for (int ks = 0; ks < 8; ++ks) {
-    f.qn[ks] = lds_read_b128(ln.q_nat[ks] + off + SOFF);
-    f.dn[ks] = lds_read_b128(ln.do_nat[ks] + off + SOFF);
-  }
-}
-
-// Start values of the score accumulators: register v of a score tile is query row
-// 16*(v/8) + 8*h + v%8 of the step; s starts at -lse/scale and dp at -delta of that row.
-template <int SROW>
-__device__ __forceinline__ void dkdv_load_init(const DkvLane& ln, unsigned off_row, floatx16_t& s, floatx16_t& dp) {
-#pragma unroll
-  for (int kstep = 0; kstep < 2; ++kstep)
-#pragma unroll
-    for (int half4 = 0; half4 < 2; ++half4) {
-      const unsigned o = off_row + SROW + (16 * kstep + 4 * half4) * 4;
-      const floatx4_t lv = lds_read_f32x4(ln.lse_addr + o), dv4 = lds_read_f32x4(ln.delta_addr + o);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) { s[8 * kstep + 4 * half4 + e] = lv[e]; dp[8 * kstep + 4 * half4 + e] = dv4[e]; }
-    }
-}
-
-template <int SOFF>
-__device__ __forceinline__ void dkdv_load_tr(const DkvLane& ln, unsigned off, DkvTrFrags& f) {
-#pragma unroll
-  for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-    for (int kstep = 0; kstep < 2; ++kstep) {
-      f.qtr[kstep][dt] = concat_tr(lds_read_tr16_addr(ln.q_tr[dt][0] + off + SOFF + kstep * 16 * 256),
-                                   lds_read_tr16_addr(ln.q_tr[dt][1] + off + SOFF + kstep * 16 * 256));
-      f.dtr[kstep][dt] = concat_tr(lds_read_tr16_addr(ln.do_tr[dt][0] + off + SOFF + kstep * 16 * 256),
-                                   lds_read_tr16_addr(ln.do_tr[dt][1] + off + SOFF + kstep * 16 * 256));
-    }
-}
-
-__device__ __forceinline__ void dkdv_scores(const DkvFrags& f, const bf16x8_t (&kf)[8], const bf16x8_t (&vf)[8],
-                                            floatx16_t& s, floatx16_t& dp) {
-#pragma unroll
-  for (int ks = 0; ks < 8; ++ks) {
-    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.qn[ks], kf[ks], s, 0, 0, 0);
-    dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.dn[ks], vf[ks], dp, 0, 0, 0);
-  }
-}
-
-__device__ __forceinline__ void dkdv_accumulate(const DkvTrFrags& f, const bf16x8_t (&pf)[2], const bf16x8_t (&dsf)[2],
-                                                floatx16_t (&dk)[4], floatx16_t (&dv)[4]) {
-#pragma unroll
-  for (int kstep = 0; kstep < 2; ++kstep)
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt) {
-      dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.dtr[kstep][dt], pf[kstep], dv[dt], 0, 0, 0);
-      dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.qtr[kstep][dt], dsf[kstep], dk[dt], 0, 0, 0);
-    }
-}
-
-// One 64-query tile.  Order of the phases (A, B = first / second 32 queries):
-//   read rows(A) | S,dP(A) ; read rows(B), transposed(A) | S,dP(B) + softmax(A) |
-//   dV,dK(A) + softmax(B) ; read transposed(B) | dV,dK(B)
-// SLOT: ring slot as a compile-time constant (then off / off_row are 0), or -1 for run-time offsets.
-template <bool MASK, int SOFF, int SROW>
-__device__ __forceinline__ void dkdv_tile(const DkvLane& ln, unsigned off, unsigned off_row,
-                                          const bf16x8_t (&kf)[8], const bf16x8_t (&vf)[8],
-                                          floatx16_t (&dk)[4], floatx16_t (&dv)[4], float c, int h, int left) {
-  DkvFrags nat_a, nat_b;
-  DkvTrFrags tr_a, tr_b;
-  floatx16_t s_a, dp_a, s_b, dp_b;
-  bf16x8_t pf_a[2], dsf_a[2], pf_b[2], dsf_b[2];
-  dkdv_load_nat<SOFF>(ln, off, nat_a);
-  dkdv_load_init<SROW>(ln, off_row, s_a, dp_a);
-  __builtin_amdgcn_sched_barrier(0);
-  dkdv_load_nat<SOFF + 8192>(ln, off, nat_b);        // in flight while S, dP of A are computed
-  dkdv_load_init<SROW + 128>(ln, off_row, s_b, dp_b);
-  dkdv_scores(nat_a, kf, vf, s_a, dp_a);
-  __builtin_amdgcn_sched_barrier(0);
-  dkdv_load_tr<SOFF>(ln, off, tr_a);                 // in flight while S, dP of B are computed
-  dkdv_scores(nat_b, kf, vf, s_b, dp_b);
-  softmax_bwd_rows<MASK>(s_a, dp_a, c, h, left, pf_a, dsf_a);
-  __builtin_amdgcn_sched_barrier(0);
-  dkdv_load_tr<SOFF + 8192>(ln, off, tr_b);          // in flight while dV, dK of A are accumulated
-  dkdv_accumulate(tr_a, pf_a, dsf_a, dk, dv);
-  softmax_bwd_rows<MASK>(s_b, dp_b, c, h, left - 32, pf_b, dsf_b);
-  __builtin_amdgcn_sched_barrier(0);
-  dkdv_accumulate(tr_b, pf_b, dsf_b, dk, dv);
-}
-
-template <int NW>
-__global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_pipe_kernel(
-    const unsigned short* __restrict__ d_oh, const unsigned short* __restrict__ qh,
-    const unsigned short* __restrict__ kh, const unsigned short* __restrict__ vh,
-    const float* __restrict__ neg_lse_over_scale, const float* __restrict__ neg_delta,
-    const int32_t* __restrict__ cu_q, const int32_t* __restrict__ cu_k,
-    const int32_t* __restrict__ tile_start, int M, int64_t Nq, int64_t Nk, int H, float scale,
-    int tiles_per_head, unsigned short* __restrict__ d_kh, unsigned short* __restrict__ d_vh) {
-  constexpr int BK = NW * 32;
-  constexpr int kDmaPerTile = 2 * (16 / NW) + 2;
-  __shared__ __attribute__((aligned(1024))) unsigned short Qs[kPipeNBuf][64 * kHeadDim];
-  __shared__ __attribute__((aligned(1024))) unsigned short dOs[kPipeNBuf][64 * kHeadDim];
-  __shared__ __attribute__((aligned(256))) float Ls[kPipeNBuf][64];   // -lse / scale
-  __shared__ __attribute__((aligned(256))) float Ds[kPipeNBuf][64];   // -delta
-  __shared__ int s_start[MOGA_MAX_GROUPS + 1];
-  __shared__ int s_found;
-
-  const int64_t total = (int64_t)H * tiles_per_head;
-  const int64_t work = xcd_work_index(blockIdx.x, total);
-  if (work >= total) return;
-  const int head = (int)(work / tiles_per_head);
-  const int tile = (int)(work - (int64_t)head * tiles_per_head);
-  TileInfo ti;   // tiles run over the key rows of the groups
-  if (tile_start) {
-    if (!find_tile_presummed(tile_start, cu_k, M, BK, tile, ti)) return;
-  } else if (!find_tile(cu_k, M, BK, tile, s_start, &s_found, ti)) {
-    return;
-  }
-  const int ge = ti.row_end, k0 = ti.tile_row;   // key rows of the group end at ge
-  const int gs = cu_q[ti.group];                 // first query row of the group
-  const int n = cu_q[ti.group + 1] - gs;         // number of queries
-
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-  const int r = lane & 31, h = lane >> 5;
-  const int64_t head_off = (int64_t)head * Nk;    // key-side tensors (kh, vh, d_kh, d_vh)
-  const int64_t head_off_q = (int64_t)head * Nq;  // query-side tensors (qh, d_oh, lse, delta)
-  const float c = scale * 1.4426950408889634f;
-
-  if (n <= 0) {   // keys without queries: zero gradient (block-uniform branch)
-    const int krow = k0 + wave * 32 + r;
-    if (krow < ge) {
-      uintx4_t* dk4 = (uintx4_t*)(d_kh + (head_off + krow) * kHeadDim + 64 * h);
-      uintx4_t* dv4 = (uintx4_t*)(d_vh + (head_off + krow) * kHeadDim + 64 * h);
-      const uintx4_t z = {0u, 0u, 0u, 0u};
-#pragma unroll
-      for (int i = 0; i < 8; ++i) { dk4[i] = z; dv4[i] = z; }
-    }
-    return;
-  }
-
-  // K, V fragments of this wave's 32 key rows: B operand, lane (r, h) holds row r, d = 16*ks + 8*h + 0..7
-  const int krow = k0 + wave * 32 + r;
-  const int krow_c = krow < ge ? krow : ge - 1;
-  bf16x8_t kf[8], vf[8];
-  {
-    const unsigned short* kp = kh + (head_off + krow_c) * kHeadDim + 8 * h;
-    const unsigned short* vp = vh + (head_off + krow_c) * kHeadDim + 8 * h;
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      kf[ks] = *(const bf16x8_t*)(kp + 16 * ks);
-      vf[ks] = *(const bf16x8_t*)(vp + 16 * ks);
-    }
-  }
-
-  PipeDma dma;   // "k" = Q rows, "v" = dO rows of this head's group
-  dma.kbase = uniform_ptr(qh + (head_off_q + gs) * kHeadDim);
-  dma.vbase = uniform_ptr(d_oh + (head_off_q + gs) * kHeadDim);
-  dma.lds_k = lds_addr_uniform(&Qs[0][0]) + wave * 1024;
-  dma.lds_v = lds_addr_uniform(&dOs[0][0]) + wave * 1024;
-  dma.row0 = 4 * wave + (lane >> 4);
-  dma.chunk_off = (unsigned)(((lane & 15) ^ lds_swizzle(dma.row0)) * 16);
-  dma.last_row = n - 1;
-  const void* lbase = uniform_ptr(neg_lse_over_scale + head_off_q + gs);
-  const void* dbase = uniform_ptr(neg_delta + head_off_q + gs);
-  const unsigned lds_l = lds_addr_uniform(&Ls[0][0]), lds_d = lds_addr_uniform(&Ds[0][0]);
-  // every wave issues the (identical) 64-float lse / delta loads so that all waves count alike
-  auto issue_tile = [&](int T) {
-    const int slot = T & 3;
-    pipe_issue_tile<NW>(dma, 64 * T, slot);
-    const unsigned roff = (unsigned)min(64 * T + lane, n - 1) * 4u;
-    lds_dma4_soff(lbase, roff, lds_l + slot * 256);
-    lds_dma4_soff(dbase, roff, lds_d + slot * 256);
-  };
-#pragma unroll
-  for (int t = 0; t <= kPipeAhead; ++t) issue_tile(t);
-
-  DkvLane ln;
-  {
-    const int qrow_a = swap_bits_2_3(r);
-    const int q_sw = lds_swizzle(qrow_a);
-    const unsigned qb = (unsigned)(uintptr_t)&Qs[0][0];
-    const unsigned db = (unsigned)(uintptr_t)&dOs[0][0];
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      ln.q_nat[ks] = qb + qrow_a * 256 + (((2 * ks + h) ^ q_sw) << 4);
-      ln.do_nat[ks] = db + qrow_a * 256 + (((2 * ks + h) ^ q_sw) << 4);
-    }
-    const int tr_r = 8 * h + ((lane & 15) >> 2);
-    const int tr_c = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
-    const int tr_e = 4 * (lane & 1);
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt) {
-      const unsigned o0 = tr_e * 2 + tr_r * 256 + (((4 * dt + tr_c) ^ lds_swizzle(tr_r)) << 4);
-      const unsigned o1 = tr_e * 2 + (tr_r + 4) * 256 + (((4 * dt + tr_c) ^ lds_swizzle(tr_r + 4)) << 4);
-      ln.q_tr[dt][0] = qb + o0;
-      ln.q_tr[dt][1] = qb + o1;
-      ln.do_tr[dt][0] = db + o0;
-      ln.do_tr[dt][1] = db + o1;
-    }
-    ln.lse_addr = (unsigned)(uintptr_t)&Ls[0][0] + 8 * h * 4;
-    ln.delta_addr = (unsigned)(uintptr_t)&Ds[0][0] + 8 * h * 4;
-  }
-
-  floatx16_t dk[4], dv[4];
-#pragma unroll
-  for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) { dk[dt][v] = 0.f; dv[dt][v] = 0.f; }
-
-  const int nfull = n >> 6;   // tiles whose 64 queries are all inside the group
-  int T = 0;
-#define MOGA_DKDV_TILE(B)                                                        \
-  __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * kPipeAhead));              \
-  __syncthreads();                                                               \
-  issue_tile(T + (B) + 1 + kPipeAhead);                                          \
-  dkdv_tile<false, (B) * kPipeTileBytes, (B) * 256>(ln, 0, 0, kf, vf, dk, dv, c, h, 64);
-  for (; T + 4 <= nfull; T += 4) {   // four tiles per iteration: every LDS offset is an immediate
-    MOGA_DKDV_TILE(0)
-    MOGA_DKDV_TILE(1)
-    MOGA_DKDV_TILE(2)
-    MOGA_DKDV_TILE(3)
-  }
-#undef MOGA_DKDV_TILE
-  for (; T < nfull; ++T) {
-    __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * kPipeAhead));
-    __syncthreads();
-    issue_tile(T + 1 + kPipeAhead);
-    dkdv_tile<false, 0, 0>(ln, ((unsigned)T & 3u) * kPipeTileBytes, ((unsigned)T & 3u) * 256, kf, vf, dk, dv, c, h, 64);
-  }
-  if (n & 63) {   // last, partial tile: masked queries contribute zero
-    __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * kPipeAhead));
-    __syncthreads();
-    dkdv_tile<true, 0, 0>(ln, ((unsigned)T & 3u) * kPipeTileBytes, ((unsigned)T & 3u) * 256, kf, vf, dk, dv, c, h,
-                          n - 64 * T);
-  }
-
-  __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // drain the look-ahead loads before the LDS is released
-  if (krow < ge) {
-    unsigned short* dkp = d_kh + (head_off + krow) * kHeadDim + 4 * h;
-    unsigned short* dvp = d_vh + (head_off + krow) * kHeadDim + 4 * h;
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-      for (int b = 0; b < 4; ++b) {
-        uintx2_t pk = {pack_bf16x2(dk[dt][4 * b] * scale, dk[dt][4 * b + 1] * scale),
-                       pack_bf16x2(dk[dt][4 * b + 2] * scale, dk[dt][4 * b + 3] * scale)};
-        uintx2_t pv = {pack_bf16x2(dv[dt][4 * b], dv[dt][4 * b + 1]),
-                       pack_bf16x2(dv[dt][4 * b + 2], dv[dt][4 * b + 3])};
-        *(uintx2_t*)(dkp + 32 * dt + 8 * b) = pk;
-        *(uintx2_t*)(dvp + 32 * dt + 8 * b) = pv;
-      }
-  }
-}
-
-// ---------------------------------------------------------------------------------------
 // dK, dV with two waves per SIMD: the four products are split between two waves that own the
 // same 32 key rows.  Wave A (waves 0-3) holds K and the dV^T accumulators: it computes S = Q K^T,
 // P = exp2(c*S - lse*log2e), hands P to its partner through LDS and accumulates dV^T += dO^T P.
@@ -693,10 +395,15 @@ __device__ __forceinline__ void ab_take_p(const AbLane& ln, const floatx16_t& dp
 //   A: S(u0), S(u1) | P -> LDS, stamp          | dV(u0), dV(u1)
 //   B: dP(u0), dP(u1) | wait for the stamp, dS = P * dP | dK(u0), dK(u1)
 // `left`: valid query rows of the tile (MASK only).  The stamp of tile t is t + 1.
+// The wait of B is bounded: after `spin_limit` polls it records a give-up in *status and goes on
+// with whatever P holds (wrong numbers, but the kernel drains normally and the host can tell).
+// Progress does not depend on the bound: A publishes the stamp of tile t before it reaches the
+// block barrier of tile t + 1 and never waits for B anywhere else, and the single P buffer of a
+// pair is only rewritten after that barrier, which B reaches only after it has consumed P.
 template <bool MASK, int SOFF, int SROW>
 __device__ __forceinline__ void ab_tile(const AbLane& ln, int role, unsigned off, unsigned off_row,
                                         const bf16x8_t (&kvf)[8], floatx16_t (&acc)[4], float c, int h, int left,
-                                        int* flag, int tile_no) {
+                                        int* flag, int tile_no, int spin_limit, int* status) {
   floatx16_t sc[2];   // S (A) or dP (B) of the two 32-query units
   bf16x8_t bop[2][2]; // B operand of the second product: P (A) or dS (B), per unit and 16-query step
   bf16x8_t tr0[2][4], tr1[2][4];
@@ -709,7 +416,14 @@ __device__ __forceinline__ void ab_tile(const AbLane& ln, int role, unsigned off
     ab_make_p<MASK>(ln, sc[1], c, h, left, 1, bop[1]);
     __hip_atomic_store(flag, tile_no, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);   // P of this tile is in LDS
   } else {
-    while (__hip_atomic_load(flag, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < tile_no) __builtin_amdgcn_s_sleep(1);
+    int polls = 0;
+    while (__hip_atomic_load(flag, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < tile_no) {
+      if (++polls > spin_limit) {   // wave-uniform
+        if ((threadIdx.x & 63) == 0) atomicOr(status, 1);
+        break;
+      }
+      __builtin_amdgcn_s_sleep(1);
+    }
     ab_take_p(ln, sc[0], 0, bop[0]);
     ab_take_p(ln, sc[1], 1, bop[1]);
   }
@@ -726,7 +440,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dkdv_ab_kernel(
     const int32_t* __restrict__ cu_q, const int32_t* __restrict__ cu_k,
     const int32_t* __restrict__ tile_start, int M, int64_t Nq, int64_t Nk, int H, float scale,
     int tiles_per_head, unsigned short* __restrict__ d_kh, unsigned short* __restrict__ d_vh,
-    const int32_t* __restrict__ perm = nullptr) {
+    int spin_limit, int* __restrict__ status, const int32_t* __restrict__ perm = nullptr) {
   constexpr int NW = 8;
   constexpr int BK = 128;                          // 4 pairs of waves x 32 keys
   constexpr int kDmaPerTile = 2 * (16 / NW) + 2;
@@ -846,7 +560,8 @@ __global__ __launch_bounds__(512) void attn_bwd_dkdv_ab_kernel(
   __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * kPipeAhead));              \
   __syncthreads();                                                               \
   issue_tile(T + (B) + 1 + kPipeAhead);                                          \
-  ab_tile<false, (B) * kPipeTileBytes, (B) * 256>(ln, role, 0, 0, kvf, acc, c, h, 64, flag, T + (B) + 1);
+  ab_tile<false, (B) * kPipeTileBytes, (B) * 256>(ln, role, 0, 0, kvf, acc, c, h, 64, flag, T + (B) + 1, \
+                                                  spin_limit, status);
   for (; T + 4 <= nfull; T += 4) {   // four tiles per iteration: every LDS offset is an immediate
     MOGA_AB_TILE(0)
     MOGA_AB_TILE(1)
@@ -859,13 +574,13 @@ __global__ __launch_bounds__(512) void attn_bwd_dkdv_ab_kernel(
     __syncthreads();
     issue_tile(T + 1 + kPipeAhead);
     ab_tile<false, 0, 0>(ln, role, ((unsigned)T & 3u) * kPipeTileBytes, ((unsigned)T & 3u) * 256, kvf, acc, c, h, 64,
-                         flag, T + 1);
+                         flag, T + 1, spin_limit, status);
   }
   if (n & 63) {   // last, partial tile: masked queries get P = 0 and contribute nothing
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * kPipeAhead));
     __syncthreads();
     ab_tile<true, 0, 0>(ln, role, ((unsigned)T & 3u) * kPipeTileBytes, ((unsigned)T & 3u) * 256, kvf, acc, c, h,
-                        n - 64 * T, flag, T + 1);
+                        n - 64 * T, flag, T + 1, spin_limit, status);
   }
 
   __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // drain the look-ahead loads before the LDS is released

@@ -154,6 +154,9 @@ static int check_attn_args(int64_t Nq, int64_t Nk, int H, int D, int M, float so
   if (Nq >= ((int64_t)1 << 31) || Nk >= ((int64_t)1 << 31)) return MOGA_ERR_UNSUPPORTED;
   if (dtype == MOGA_BF16 && D != 128) return MOGA_ERR_UNSUPPORTED;
   if (dtype == MOGA_F32 && D != 64 && D != 128) return MOGA_ERR_UNSUPPORTED;
+  // the bf16 kernels form per-lane byte offsets `row * 256` in 32 bits, relative to the first row
+  // of a group: a group (hence a tensor) must have fewer than 2^24 rows
+  if (dtype == MOGA_BF16 && (Nq >= ((int64_t)1 << 24) || Nk >= ((int64_t)1 << 24))) return MOGA_ERR_UNSUPPORTED;
   return MOGA_OK;
 }
 

@@ -30,6 +30,9 @@ class Workload:
     dtype: str        # "f32" | "bf16": storage type of X, Q, K, V, dO
     hidden: str       # "iid" | "mixture" | "mixture_unaligned"
     weights: str = "uniform"   # mixture component weights: "uniform" | "zipf"
+    zipf_s: float = 1.1        # exponent of the Zipf weights: component k has weight (k + 1)^-zipf_s
+    absent: int = 0            # this many of the rarest components get weight 0: their groups only
+                               # receive tokens that the noise pushes there (near-empty groups)
     align: float = 4.0         # length of the component mean along its router row
     noise_var: float = 1.0     # variance of the isotropic noise added to the mean
     backward: bool = False
@@ -57,6 +60,12 @@ WORKLOADS = {
                    seed=1003, grid="64x30x52"),
     "C3b": Workload("C3b", 99840, 40, 128, 5120, 16, "bf16", "mixture_unaligned",
                     weights="zipf", seed=1013, grid="64x30x52"),
+    # C3 shapes, forward + backward, with the ~50x span of group sizes that configuration 3 asks
+    # for and near-empty groups: Zipf(1.1) over 16 components spans only 16^1.1 = 21x, so the
+    # exponent is raised to 1.45 (14^1.45 = 46x over the 14 components that are present) and the
+    # two rarest components are left out, so that two groups receive only stray tokens
+    "C3u": Workload("C3u", 99840, 40, 128, 5120, 16, "bf16", "mixture", weights="zipf",
+                    zipf_s=1.45, absent=2, align=5.0, backward=True, seed=1023, grid="64x30x52"),
     # paper-scale context: 372 frames
     "C4": Workload("C4", 580320, 40, 128, 5120, 32, "bf16", "mixture", noise_var=0.5,
                    seed=1004, grid="372x30x52"),
@@ -114,7 +123,9 @@ def make_inputs(w: Workload, device="cpu"):
         comp = torch.zeros(N, dtype=torch.int64, device=dev)
     else:
         if w.weights == "zipf":
-            pk = torch.arange(1, M + 1, dtype=torch.float64, device=dev) ** -1.1
+            pk = torch.arange(1, M + 1, dtype=torch.float64, device=dev) ** -w.zipf_s
+            if w.absent > 0:
+                pk[M - w.absent:] = 0.0
         else:
             pk = torch.ones(M, dtype=torch.float64, device=dev)
         pk = (pk / pk.sum()).to(torch.float32)

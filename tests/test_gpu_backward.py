@@ -175,3 +175,41 @@ def test_single_group_backward_has_zero_router_gradient():
     f, b, fg, bg = run_fwd_bwd(w)
     assert torch.all(bg["d_w"] == 0)
     P.assert_close_f32(P.to64(bg["d_q"]), b["dQ"], "dQ (M=1)")
+
+
+def test_bounded_wait_of_the_dkdv_kernel_reports_a_give_up_and_never_fires_normally():
+    """The partner wait inside the dK/dV kernel is bounded: the status word of the workspace reads 0
+    after a normal run; with the poll limit forced to 0 from the host every unsatisfied wait gives up,
+    the word becomes nonzero and the kernel still drains; afterwards a normal run is correct again."""
+    sizes = [700, 130, 2049]
+    q, k, v, dA, cu, scale = attn_bwd_case(sizes, 2, 128, "bf16", seed=21)
+    q64, k64, v64, dA64 = (P.to64(t) for t in (q, k, v, dA))
+    A, lse = orc.group_attention(q64, k64, v64, cu, scale)
+    dQ, dK, dV = orc.group_attention_bwd(q64, k64, v64, dA64, cu, scale)
+    tohat = lambda t: t.permute(1, 0, 2).contiguous().cuda()
+    oh = torch.from_numpy(P.hat(A)).to(torch.bfloat16).cuda()
+    lse_d = torch.from_numpy(np.ascontiguousarray(lse.T)).float().cuda()
+    args = (tohat(dA), tohat(q), tohat(k), tohat(v), oh, lse_d, torch.from_numpy(cu).cuda(), scale)
+    N, H = sum(sizes), 2
+    ws = torch.empty(mg.workspace_bytes(mg.OP_ATTN_BWD, N, H, 128, len(sizes), 0, mg.MOGA_BF16),
+                     dtype=torch.uint8, device="cuda").fill_(0xAB)
+    status = mg.attn_bwd_status(ws, N, H)
+
+    def run_and_check():
+        d_qh, d_kh, d_vh = mg.moga_group_attn_bwd(*args, ws=ws)
+        torch.cuda.synchronize()
+        assert int(status.item()) == 0
+        for name, got, ref in (("dQ", d_qh, dQ), ("dK", d_kh, dK), ("dV", d_vh, dV)):
+            check(P.unhat(got), ref, name, "bf16")
+
+    run_and_check()
+    try:
+        mg.set_spin_limit(0)
+        mg.moga_group_attn_bwd(*args, ws=ws)
+        torch.cuda.synchronize()            # the kernel drained
+        flagged = int(status.item())
+    finally:
+        mg.set_spin_limit(1 << 24)
+    say(f"  status word with the poll limit forced to 0: {flagged}")
+    assert flagged != 0
+    run_and_check()

@@ -136,12 +136,18 @@ def attn_case(sizes, H, D, dtype, seed, scale=None, peaked=False):
     tdt = torch.float32 if dtype == "f32" else torch.bfloat16
     q, k, v = (torch.randn((N, H, D), generator=g).to(tdt) for _ in range(3))
     cu = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
-    if peaked:   # one dominant key per query: K = 4 * Q shifted by one inside each group
-        kk = q.clone().float()
+    if peaked:
+        # Clusters of 8 consecutive rows of a group share a direction b: q = (b + e_q) / sqrt(2),
+        # k = (b + e_k) / sqrt(2), still unit variance.  A query's score is about 5.7 +- 1 on the 8
+        # keys of its cluster and N(0, 1) elsewhere, so a handful of keys share most of the softmax
+        # mass with unequal weights: |O| is of the order of |V| and the rounding of P matters.
+        qq, kk = q.float(), k.float()
         for s, e in zip(cu[:-1], cu[1:]):
-            if e - s > 1:
-                kk[s:e] = torch.roll(q[s:e].float(), 1, 0)
-        k = (4 * kk).to(tdt)
+            n = int(e - s)
+            base = torch.randn(((n + 7) // 8, H, D), generator=g).repeat_interleave(8, dim=0)[:n]
+            qq[s:e] = (base + qq[s:e]) / math.sqrt(2.0)
+            kk[s:e] = (base + kk[s:e]) / math.sqrt(2.0)
+        q, k = qq.to(tdt), kk.to(tdt)
     scale = scale if scale is not None else D ** -0.5
     return q, k, v, cu, scale
 
@@ -174,13 +180,24 @@ def test_group_attention_forward_matches_oracle(sizes, H, D, dtype):
 
 
 def test_group_attention_bf16_peaked_rows_have_teeth():
-    """One dominant key per query, so |O| ~ |V|: the 2e-2 max-abs bound is not vacuous here."""
-    q, k, v, cu, scale = attn_case([700, 300, 1000], 2, 128, "bf16", seed=5, peaked=True)
+    """A handful of keys share each query's softmax mass, so |O| ~ |V| and P's rounding to bf16
+    shows: the stated 2e-2 max-abs bound is not vacuous here (and the softmax is not one-hot)."""
+    sizes = [700, 300, 1000, 8, 3]
+    q, k, v, cu, scale = attn_case(sizes, 2, 128, "bf16", seed=5, peaked=True)
     A, _ = orc.group_attention(P.to64(q), P.to64(k), P.to64(v), cu, scale)
-    assert np.abs(A).max() > 2.0
+    # shape of the softmax in the largest group, head 0 (a property of the input, not a reference)
+    s0, e0 = int(cu[2]), int(cu[3])
+    S = scale * P.to64(q)[s0:e0, 0] @ P.to64(k)[s0:e0, 0].T
+    Pm = np.exp(S - S.max(1, keepdims=True))
+    Pm /= Pm.sum(1, keepdims=True)
+    top, top8 = np.median(Pm.max(1)), np.median(np.sort(Pm, 1)[:, -8:].sum(1))
+    say(f"  peaked case: median top-1 prob {top:.3f}, median top-8 mass {top8:.3f}, max|A| {np.abs(A).max():.2f}, "
+        f"rms A {np.sqrt((A ** 2).mean()):.3f}")
+    assert 0.05 < top < 0.8 and top8 > 0.5          # peaked, but several keys share the mass
+    assert np.sqrt((A ** 2).mean()) > 0.25          # outputs of the order of the values
     tohat = lambda t: t.permute(1, 0, 2).contiguous().cuda()
     oh, _ = mg.moga_group_attn_fwd(tohat(q), tohat(k), tohat(v), torch.from_numpy(cu).cuda(), scale)
-    say("  peaked error", P.assert_close_bf16(P.unhat(oh), A, "peaked attention output", abs_tol=3e-2))
+    say("  peaked error", P.assert_close_bf16(P.unhat(oh), A, "peaked attention output"))   # the stated 2e-2
 
 
 def test_group_attention_constant_values_return_the_value():
@@ -241,18 +258,24 @@ def test_config1_fp32_forward_every_element():
     say(f"  O rel err {e:.3e}")
 
 
-def test_config2_shape_bf16_forward_reduced_tokens():
-    """C2's widths (12 heads, head_dim 128, d_model 1536, M = 8) on 6 latent frames."""
-    w = wl.scaled(wl.WORKLOADS["C2"], N=6 * 1560)
-    say("C2 (6 frames) full forward")
+@pytest.mark.timeout(600)
+def test_config2_bf16_forward_every_element():
+    """Configuration 2 at its stated size: N = 32,760 (21 frames), 12 heads, head_dim 128,
+    d_model 1536, M = 8; every output element against the full oracle."""
+    w = wl.WORKLOADS["C2"]
+    say(f"C2 full forward: N={w.N} H={w.H}")
     inp, f, out = run_forward(w)
     bad = P.check_assignment(out["group"].cpu().numpy(), f)
+    say(f"  argmax mismatches (margin < 1e-5 only): {len(bad)}; counts {f['counts'].tolist()}")
     if not bad:
         for name in ("counts", "cu_seqlens", "perm", "inv_perm"):
             assert np.array_equal(out[name].cpu().numpy(), f[name]), name
+        e = P.assert_close_bf16(P.unhat(out["oh"]), f["A"], "A")
+        say(f"  A (ungated, sorted order) error {e}")
     keep = np.ones(w.N, bool)
     keep[[m[0] for m in bad]] = False
-    say("  counts", f["counts"].tolist(), "O error", P.assert_close_bf16(P.to64(out["o"])[keep], f["O"][keep], "O"))
+    np.testing.assert_allclose(P.to64(out["gate"])[keep], f["gate"][keep], rtol=3e-5)
+    say("  O error", P.assert_close_bf16(P.to64(out["o"])[keep], f["O"][keep], "O"))
 
 
 def test_single_group_is_full_attention_on_the_gpu():

@@ -4,8 +4,8 @@ The whole oracle is out of reach at these sizes (33-750 TFLOP), so:
   * routing, histogram, offsets and permutation are checked for ALL tokens;
   * attention outputs, lse and dQ are checked on sampled query rows (each attended against every
     key of its group, so the sampled rows are exact);
-  * dK, dV are checked in full for one head of the smallest group;
-  * the scatter, its backward and d_gate are checked on sampled tokens;
+  * dK, dV are checked in full for several heads of the two smallest groups and a mid-size one;
+  * the scatter, its backward and d_gate (1,024 tokens, all heads) are checked on sampled tokens;
   * the router weight gradient is checked in full through the C ABI with a seeded upstream d_gate.
 Inputs are generated on the GPU from the workload seed and copied to the host for the oracle.
 """
@@ -32,7 +32,7 @@ def oracle_route_all(X, W, chunk=65536):
     return {k: np.concatenate([p[k] for p in parts]) for k in parts[0]}
 
 
-NAMES = ["C3b", "C5", "C4b"]
+NAMES = ["C3b", "C3u", "C5", "C4b"]
 _cache = {}
 
 
@@ -56,8 +56,21 @@ def run(name):
          "perm_t": torch.from_numpy(idx["perm"].astype(np.int64)).cuda(), "gate64": P.to64(fg["gate"])}
     nonempty = [g for g in range(w.M) if idx["counts"][g] > 0]
     c["by_size"] = sorted(nonempty, key=lambda g: idx["counts"][g])
+    say(f"  group sizes (sorted): {sorted(idx['counts'].tolist())}")
     _cache[name] = c
     return c
+
+
+def test_unbalanced_workload_spans_fifty_times_with_near_empty_groups():
+    """Configuration 3 asks for group sizes spanning ~50x; C3u realises that with near-empty groups."""
+    c = run("C3u")
+    counts = np.sort(c["idx"]["counts"])
+    main = counts[counts >= 256]
+    span = main.max() / main.min()
+    tiny = counts[counts < 64]
+    say(f"  C3u histogram {counts.tolist()}: span of the {len(main)} main groups {span:.1f}x, "
+        f"{len(tiny)} near-empty groups {tiny.tolist()}")
+    assert span >= 40.0 and len(tiny) >= 1 and counts.sum() == c["w"].N
 
 
 @pytest.mark.timeout(600)
@@ -118,36 +131,52 @@ def test_sampled_attention_rows_and_their_gradients(name):
             assert rm <= P.BF16_REL_MAX and rl <= P.BF16_REL_L2
 
 
-@pytest.mark.timeout(600)
+@pytest.mark.timeout(900)
 @pytest.mark.parametrize("name", [n for n in NAMES if wl.WORKLOADS[n].backward])
-def test_gate_gradient_and_one_full_group_of_dk_dv(name):
+def test_gate_gradient_on_1024_tokens_and_three_full_groups_of_dk_dv(name):
     c = run(name)
     w, bg, idx, perm_t, gate64 = c["w"], c["bg"], c["idx"], c["perm_t"], c["gate64"]
     Q, K, V, dO = (c["inp"][k] for k in ("Q", "K", "V", "dO"))
     rng = np.random.default_rng(w.seed + 2)
-    perm, cu = idx["perm"], idx["cu_seqlens"]
-    g = c["by_size"][0]                      # smallest group
-    s, e = int(cu[g]), int(cu[g + 1])
-    members = perm_t[s:e]
-    # d_gate = sum over heads of dO . A on sampled tokens of that group
-    r = np.unique(rng.choice(e - s, min(16, e - s), replace=False))
-    toks_t = torch.from_numpy(perm[s + r].astype(np.int64)).cuda()
-    dg = np.zeros(len(r))
-    for h in range(w.H):
-        out, _ = orc.softmax_attention(P.to64(Q[toks_t, h]), P.to64(K[members, h]), P.to64(V[members, h]), w.scale)
-        dg += (P.to64(dO[toks_t, h]) * out).sum(1)
-    got = P.to64(bg["d_gate"][toks_t])
-    say(f"  d_gate sample: max err / max {np.abs(got - dg).max() / np.abs(dg).max():.2e}")
-    np.testing.assert_allclose(got, dg, rtol=2e-2, atol=2e-2 * np.abs(dg).max())
-    # dK, dV in full for head 0 of that group
-    h = 0
-    dA = gate64[perm[s:e]][:, None] * P.to64(dO[members, h])
-    _, dKg, dVg = orc.softmax_attention_bwd(P.to64(Q[members, h]), P.to64(K[members, h]), P.to64(V[members, h]),
-                                            dA, w.scale)
-    for nm, ref, got in (("dK", dKg, bg["d_k"][members, h]), ("dV", dVg, bg["d_v"][members, h])):
-        rm, rl = P.rel_max(P.to64(got), ref), P.rel_l2(P.to64(got), ref)
-        say(f"  {nm} group {g} (n={e - s}) head {h}: rel max {rm:.2e}, l2 {rl:.2e}")
-        assert rm <= P.BF16_REL_MAX and rl <= P.BF16_REL_L2
+    perm, cu, by_size = idx["perm"], idx["cu_seqlens"], c["by_size"]
+    sized = [g for g in by_size if idx["counts"][g] >= 256]
+    # d_gate = sum over heads of dO . A: 1,024 tokens, half from the smallest group with at least
+    # 256 tokens (plus every token of a near-empty group, if any), half from a mid-size group
+    picks = []
+    if idx["counts"][by_size[0]] < 256:
+        picks.append((by_size[0], int(idx["counts"][by_size[0]])))
+    picks += [(sized[0], 512), (sized[len(sized) // 2], 512)]
+    worst = 0.0
+    ntok = 0
+    for g, want in picks:
+        s, e = int(cu[g]), int(cu[g + 1])
+        members = perm_t[s:e]
+        r = np.unique(rng.choice(e - s, min(want, e - s), replace=False))
+        toks_t = torch.from_numpy(perm[s + r].astype(np.int64)).cuda()
+        dg = np.zeros(len(r))
+        for h in range(w.H):
+            out, _ = orc.softmax_attention(P.to64(Q[toks_t, h]), P.to64(K[members, h]), P.to64(V[members, h]), w.scale)
+            dg += (P.to64(dO[toks_t, h]) * out).sum(1)
+        got = P.to64(bg["d_gate"][toks_t])
+        err = np.abs(got - dg).max() / np.abs(dg).max()
+        worst = max(worst, err)
+        ntok += len(r)
+        np.testing.assert_allclose(got, dg, rtol=2e-2, atol=1e-2 * np.abs(dg).max())
+    say(f"  d_gate on {ntok} tokens: worst max err / max {worst:.2e}")
+    assert ntok >= 1024
+    # dK, dV in full: the two smallest groups and a mid-size one, two heads each
+    full = [(by_size[0], 0), (by_size[0], w.H - 1), (by_size[1], 1), (by_size[1], w.H // 2),
+            (by_size[len(by_size) // 2], 2), (by_size[len(by_size) // 2], w.H - 2)]
+    for g, h in full:
+        s, e = int(cu[g]), int(cu[g + 1])
+        members = perm_t[s:e]
+        dA = gate64[perm[s:e]][:, None] * P.to64(dO[members, h])
+        _, dKg, dVg = orc.softmax_attention_bwd(P.to64(Q[members, h]), P.to64(K[members, h]), P.to64(V[members, h]),
+                                                dA, w.scale)
+        for nm, ref, got in (("dK", dKg, bg["d_k"][members, h]), ("dV", dVg, bg["d_v"][members, h])):
+            rm, rl = P.rel_max(P.to64(got), ref), P.rel_l2(P.to64(got), ref)
+            say(f"  {nm} group {g} (n={e - s}) head {h}: rel max {rm:.2e}, l2 {rl:.2e}")
+            assert rm <= P.BF16_REL_MAX and rl <= P.BF16_REL_L2
 
 
 @pytest.mark.timeout(600)
@@ -184,6 +213,69 @@ def test_balancing_loss_over_all_tokens(name):
     np.testing.assert_allclose(P.to64(prob), Pm, rtol=1e-6)
     dg = mg.moga_balance_loss_bwd(group_t, frac, 0.1)
     np.testing.assert_allclose(P.to64(dg), orc.balance_loss_bwd(rt["group"], w.M, 0.1), rtol=2e-6)
+
+
+@pytest.mark.timeout(900)
+def test_three_branch_block_at_the_benchmark_geometry_sampled_rows():
+    """The block of Section 3.2 as `bench.py --block` runs it (C4b inputs, 372 x 30 x 52 grid, 12 shots,
+    8 x 13 windows, one run per shot): the static index lists are compared in full with the oracle's,
+    the block output and dQ on sampled (token, head) rows, each row attended against every key of its
+    three groups."""
+    from oracle import stga_oracle as sto
+    c = run("C4b")
+    c["fg"] = c["bg"] = None            # make room: the block holds its own copies of everything
+    torch.cuda.empty_cache()
+    w, inp, rt, idx = c["w"], c["inp"], c["rt"], c["idx"]
+    assert not c["bad"]
+    T, Hh, Ww = (int(v) for v in w.grid.split("x"))
+    wh, ww, n_shots = 8, 13, 12
+    shots = np.minimum(np.arange(T) * n_shots // T, n_shots - 1)
+    si = mg.moga_stga_build_index(T, Hh, Ww, wh, ww, T, shots)
+    ref_i = sto.stga_index(T, Hh, Ww, wh, ww, T, shots)
+    for k in ("q_index", "cu_q", "kv_index", "cu_k"):
+        assert np.array_equal(si[k].cpu().numpy(), ref_i[k]), k
+    say(f"  static index: {ref_i['n_groups']} groups, {len(ref_i['kv_index'])} listed keys: bit-exact")
+    fwd = mg.visual_forward(inp["X"], inp["W"], inp["Q"], inp["K"], inp["V"], w.scale, (T, Hh, Ww), si)
+    bwd = mg.visual_backward(fwd, inp["X"], inp["W"], inp["dO"], w.scale)
+    torch.cuda.synchronize()
+    assert np.array_equal(fwd["group"].cpu().numpy(), rt["group"])
+    Q, K, V, dO = (inp[k] for k in ("Q", "K", "V", "dO"))
+    perm, cu = idx["perm"], idx["cu_seqlens"]
+    sgroup, _ = sto.stga_group_of_token(T, Hh, Ww, wh, ww, T, shots)
+    n_frame = Hh * Ww
+    rng = np.random.default_rng(w.seed + 5)
+    # tokens of the first shot (one neighbour shot), of interior shots and of the last shot
+    toks = [int(rng.integers(0, 31 * n_frame)), int(rng.integers(31 * n_frame, 62 * n_frame)),
+            int(rng.integers(5 * 31 * n_frame, 6 * 31 * n_frame)), int(rng.integers(8 * 31 * n_frame, 9 * 31 * n_frame)),
+            int(rng.integers((T - 31) * n_frame, T * n_frame)), w.N - 1]
+    worst_o = worst_q = 0.0
+    for t in toks:
+        g = int(rt["group"][t])
+        gate = float(rt["gate"][t])
+        lists = [perm[int(cu[g]):int(cu[g + 1])].astype(np.int64),
+                 ref_i["kv_index"][int(ref_i["cu_k"][sgroup[t]]):int(ref_i["cu_k"][sgroup[t] + 1])].astype(np.int64),
+                 np.arange((t // n_frame) * n_frame, (t // n_frame + 1) * n_frame)]
+        assert all(t in set(l.tolist()) for l in lists)
+        for h in (int(rng.integers(0, w.H)), w.H - 1):
+            q_row = P.to64(Q[t, h])[None, :]
+            d_row = P.to64(dO[t, h])[None, :] / 3.0
+            o_ref = np.zeros(w.D)
+            dq_ref = np.zeros(w.D)
+            for b, keys in enumerate(lists):
+                keys_t = torch.from_numpy(keys).cuda()
+                Kg, Vg = P.to64(K[keys_t, h]), P.to64(V[keys_t, h])
+                f = gate if b == 0 else 1.0            # only the dynamic branch is gated (Eq. 5)
+                out, _ = orc.softmax_attention(q_row, Kg, Vg, w.scale)
+                o_ref += f * out[0] / 3.0
+                dq_ref += orc.softmax_attention_bwd_rows(q_row, Kg, Vg, f * d_row, w.scale)[0]
+            got_o, got_q = P.to64(fwd["o"][t, h]), P.to64(bwd["d_q"][t, h])
+            eo = np.abs(got_o - o_ref).max() / np.abs(o_ref).max()
+            eq = np.abs(got_q - dq_ref).max() / np.abs(dq_ref).max()
+            worst_o, worst_q = max(worst_o, eo), max(worst_q, eq)
+            assert np.abs(got_o - o_ref).max() <= P.BF16_ABS and eo <= P.BF16_REL_MAX, (t, h, eo)
+            assert eq <= P.BF16_REL_MAX, (t, h, eq)
+    say(f"  block rows ({len(toks)} tokens x 2 heads): worst rel max error O {worst_o:.2e}, dQ {worst_q:.2e}")
+    del fwd, bwd
 
 
 def test_release_cached_run():
