@@ -27,14 +27,7 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, published
 
-# HBM bytes per call, measured with two rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE; each scaled
-# by what the same counter reads for a plain 1 GiB copy: FETCH x 2.00, WRITE x 1.00).  Summary and
-# commands: profiles/layer_C4b_hbm_traffic.md.  Only the workload it was measured on has an entry.
-MEASURED_HBM_BYTES = {
-    ("C4b", "moga_route"): 6.11e9, ("C4b", "moga_permute"): 35.7e9, ("C4b", "moga_group_attn_fwd"): 68.7e9,
-    ("C4b", "moga_unpermute"): 11.9e9, ("C4b", "moga_unpermute_bwd"): 17.9e9,
-    ("C4b", "moga_group_attn_bwd"): 220.3e9, ("C4b", "moga_permute_bwd"): 35.7e9, ("C4b", "moga_route_bwd"): 6.53e9,
-}
+BENCH_LIB = os.path.join(ROOT, "paper_2510_18692_amd", "libmoga_bench.so")
 
 
 def parse():
@@ -42,7 +35,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="C4b", help="C1, C1b, C2, C3, C3b, C4, C4b (default), C5")
+    ap.add_argument("--workload", default="C4b", help="C1, C1b, C2, C3, C3b, C3u, C4, C4b (default), C5")
     ap.add_argument("--fused", action="store_true",
                     help="use the gather-fused attention calls (no permuted tensors are materialised): permute builds "
                          "the index only, moga_fused_attn_fwd / _bwd replace gather + attention + scatter")
@@ -57,9 +50,11 @@ def parse():
                     help="--block: spatial window rows x cols x frames per run (0 = a whole shot). The default is the "
                          "4 x 4 partition of the 30 x 52 latent frame that the paper pairs with long contexts")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-measured-peaks", action="store_true",
+                    help="skip the two peak microbenchmarks (register-resident MFMA loop, plain 1 GiB copy)")
     ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run one plain 1 GiB device copy (a kernel of known traffic, used to scale "
-                         "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
+                    help="run the plain 1 GiB copy kernel even with --no-measured-peaks (a kernel of known traffic, "
+                         "used to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
 
 
@@ -89,45 +84,101 @@ def algorithmic_work(w, counts):
     return work
 
 
-def cpu_baseline(w, budget_s=20.0):
-    """The oracle as it stands, timed on this host on a bounded sample of the same workload."""
+def measured_peaks(torch):
+    """What this GPU delivers on two microbenchmarks (a second denominator beside the published peaks):
+    a register-resident bf16 MFMA loop and a plain 1 GiB copy, each timed with HIP events, best of 3."""
+    import ctypes
+    lib = ctypes.CDLL(BENCH_LIB)
+    lib.moga_bench_mfma_loop.restype = ctypes.c_double
+    lib.moga_bench_mfma_loop.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+    lib.moga_bench_copy.restype = ctypes.c_double
+    lib.moga_bench_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    st = torch.cuda.current_stream().cuda_stream
+    blocks = 1024
+    sink = torch.empty(blocks * 256, dtype=torch.float32, device="cuda")
+    src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(3)
+    dst = torch.empty_like(src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def best(fn):
+        rates = []
+        for _ in range(4):        # the first run warms up
+            e0.record()
+            amount = fn()
+            e1.record()
+            torch.cuda.synchronize()
+            assert amount > 0
+            rates.append(amount / (e0.elapsed_time(e1) * 1e-3))
+        return max(rates[1:])
+
+    tf = best(lambda: lib.moga_bench_mfma_loop(blocks, 20000, sink.data_ptr(), st)) / 1e12
+    gb = best(lambda: lib.moga_bench_copy(dst.data_ptr(), src.data_ptr(), src.numel(), st)) / 1e9
+    del sink, src, dst
+    return {"mfma_bf16_tflops": round(tf, 1), "hbm_copy_gbs": round(gb, 1),
+            "how": "register-resident 32x32x16 bf16 MFMA loop (1024 blocks x 4 waves); plain 1 GiB copy kernel"}
+
+
+def cpu_baseline(w, inp, budget_s=20.0):
+    """The oracle as it stands, timed on this host on a bounded sample of the SAME workload: routing and
+    the permutation index of all tokens, then softmax_attention (+ its backward) on whole (group, head)
+    pairs of the workload's own groups, smallest group first, until the time budget is used."""
     import numpy as np
     from oracle import moga_oracle as orc
+    from paper_2510_18692_amd import workloads as wl
     try:
         from threadpoolctl import threadpool_info
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         threads = os.cpu_count() or 1
-    rng = np.random.default_rng(7)
-    n_g = max(64, w.N // w.M)                   # one average-size group
-    n_g = min(n_g, 8192)                        # bounded: the score matrix is n_g^2 float64
-    D = w.D
-    q, k, v, dA = (rng.standard_normal((n_g, D)) for _ in range(4))
+    t64 = wl.to_numpy64
+    W64 = t64(inp["W"])
+    t_route, parts = 0.0, []
+    for s in range(0, w.N, 65536):
+        x = t64(inp["X"][s:s + 65536])          # copy to the host and widening: not timed
+        t0 = time.perf_counter()
+        parts.append(orc.route(x, W64)["group"])
+        t_route += time.perf_counter() - t0
+    group = np.concatenate(parts)
     t0 = time.perf_counter()
-    reps = 0
-    fl = 0.0
-    while True:
+    idx = orc.permute_index(group, w.M)
+    t_perm = time.perf_counter() - t0
+    import torch
+    order = sorted((g for g in range(w.M) if idx["counts"][g] > 0), key=lambda g: idx["counts"][g])
+    fl, el, done = 0.0, 0.0, []
+    for i in range(64):
+        g, h = order[i % len(order)], (7 * i) % w.H
+        n = int(idx["counts"][g])
+        if n > 24000:        # the score matrix is n^2 float64, several of them live at once
+            continue
+        members = torch.from_numpy(idx["perm"][idx["cu_seqlens"][g]:idx["cu_seqlens"][g + 1]].astype(np.int64)).to(inp["Q"].device)
+        q, k, v = (t64(inp[name][members, h]) for name in ("Q", "K", "V"))
+        dA = t64(inp["dO"][members, h]) if w.backward else None
+        t0 = time.perf_counter()
         orc.softmax_attention(q, k, v, w.scale)
-        fl += 4.0 * n_g * n_g * D
+        fl += 4.0 * n * n * w.D
         if w.backward:
             orc.softmax_attention_bwd(q, k, v, dA, w.scale)
-            fl += 10.0 * n_g * n_g * D
-        reps += 1
-        el = time.perf_counter() - t0
-        if el > budget_s or reps >= 50:
+            fl += 10.0 * n * n * w.D
+        el += time.perf_counter() - t0
+        done.append(n)
+        if el > budget_s:
             break
-    # routing sample, reported in the note only
-    nt = min(w.N, 16384)
-    X = rng.standard_normal((nt, w.d_model))
-    W = rng.standard_normal((w.M, w.d_model))
-    t1 = time.perf_counter()
-    orc.route(X, W)
-    t_route = time.perf_counter() - t1
+    from paper_2510_18692_amd import flops
+    counts = idx["counts"].tolist()
+    total = flops.group_attn_fwd_flops(counts, w.H, w.D) + (flops.group_attn_bwd_flops(counts, w.H, w.D) if w.backward else 0)
+    rate = fl / el if el > 0 else float("nan")
+    layer_s = total / rate + t_route + t_perm
     return {
-        "value": fl / el / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
-        "sample": (f"{reps} x one head of one group of {n_g} tokens (head_dim {D}), "
-                   f"{'forward+backward' if w.backward else 'forward'}, float64 numpy, {el:.1f} s; "
-                   f"routing {nt} tokens took {t_route:.2f} s"),
+        "value": rate / 1e12, "unit": "TFLOP/s", "cores": int(threads), "host_cores": os.cpu_count(), "kind": "oracle",
+        "measured_s": {"route_all_tokens": round(t_route, 2), "permute_index_all_tokens": round(t_perm, 3),
+                       "attention_sample": round(el, 2)},
+        "extrapolated_layer_s": round(layer_s, 1),
+        "sample": (f"float64 numpy oracle on this workload's own tensors: route of all {w.N} tokens {t_route:.1f} s, "
+                   f"permute_index {t_perm:.2f} s (both measured in full); softmax_attention"
+                   f"{' + softmax_attention_bwd' if w.backward else ''} on {len(done)} whole (group, head) pairs of its own groups "
+                   f"(n = {done}), {fl / 1e12:.2f} TFLOP in {el:.1f} s (measured); whole layer "
+                   f"({total / 1e12:.0f} TFLOP) by FLOP ratio: {layer_s:.0f} s (extrapolated); "
+                   f"{threads} BLAS threads on {os.cpu_count()} host cores"),
     }
 
 
@@ -266,12 +317,9 @@ def main():
 
     if args.fused:
         step = step_fused
-    if args.calibrate_copy:
-        a = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
-        b = torch.empty_like(a)
-        b.copy_(a)          # 1 GiB read + 1 GiB written
-        torch.cuda.synchronize()
-        del a, b
+    peaks = None
+    if args.calibrate_copy or not args.no_measured_peaks:
+        peaks = measured_peaks(torch)   # includes the plain 1 GiB copy (copy_kernel) that calibrates the PMC counters
     for _ in range(args.warmup):
         out = step()
         torch.cuda.synchronize()
@@ -326,7 +374,13 @@ def main():
     roof = {k: calls[dominant][k] for k in ("bound", "achieved", "peak", "unit", "frac")}
     roof["kernel"] = dominant
     roof["ms"] = calls[dominant]["ms"]
-    roof["traffic"] = MEASURED_HBM_BYTES.get((w.name, dominant))
+    # HBM bytes of that call from the tracked rocprofv3 summary of this workload (null if there is none)
+    from paper_2510_18692_amd import profiling
+    roof["traffic"] = profiling.read_call_traffic(w.name).get(dominant)
+    if peaks is not None:
+        roof["measured_peak"] = peaks
+        den = peaks["mfma_bf16_tflops"] if roof["bound"] == "mfma" else peaks["hbm_copy_gbs"]
+        roof["frac_of_measured_peak"] = round(roof["achieved"] / den, 4)
 
     from paper_2510_18692_amd import flops
     total_flops = flops.group_attn_fwd_flops(counts, w.H, w.D)
@@ -352,7 +406,7 @@ def main():
     if graph_ms is not None:
         line["graph_replay_ms_per_step"] = round(graph_ms, 4)
     if not args.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(w)
+        line["cpu_baseline"] = cpu_baseline(w, inp)
     print(json.dumps(line), flush=True)
 
 

@@ -10,6 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmoga.so")
+BENCH_LIB = os.path.join(HERE, "libmoga_bench.so")   # peak microbenchmarks for bench.py only
 EXAMPLE = os.path.join(HERE, "c_abi_example")
 SOURCES = ["api.hip", "route.hip", "permute.hip", "attn_fwd.hip", "attn_bwd.hip", "balance.hip", "static_index.hip"]
 FLAGS = [
@@ -51,6 +52,11 @@ def build(verbose: bool = False, extra_flags=()) -> str:
                        capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stdout + r.stderr)
+    # the two peak microbenchmarks bench.py reports beside the published peaks (a library of their own)
+    r = subprocess.run([hipcc, *FLAGS, *extra_flags, "-shared", os.path.join(CSRC, "bench_peaks.hip"),
+                        "-o", BENCH_LIB], capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("bench library build failed:\n" + r.stdout + r.stderr)
     # a torch-free client of the C ABI (run by the GPU tests)
     r = subprocess.run([hipcc, "--offload-arch=gfx950", "-O2", "-I", os.path.join(ROOT, "include"),
                         os.path.join(CSRC, "c_abi_example.cpp"), "-L", HERE, "-lmoga", "-Wl,-rpath,$ORIGIN",

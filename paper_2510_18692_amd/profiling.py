@@ -1,0 +1,245 @@
+"""Turns rocprofv3 output of `bench.py` runs into the short text summaries kept under profiles/,
+and reads the per-call HBM traffic back for bench.py's `roofline.traffic`.
+
+Usage (after the rocprofv3 runs named in each summary have written their CSV files):
+
+    python -m paper_2510_18692_amd.profiling layer    --workload C4b --stats S_kernel_stats.csv \\
+        --fetch F_counter_collection.csv --write W_counter_collection.csv --bench-log run.log --out-dir profiles
+    python -m paper_2510_18692_amd.profiling counters --workload C4b --stats S_kernel_stats.csv \\
+        --csv pass1_counter_collection.csv pass2_counter_collection.csv --out profiles/attn_C4b_mfma_counters.md
+
+No GPU is needed for either; nothing here is imported by the library's hot path.
+"""
+from __future__ import annotations
+
+import argparse
+import collections
+import csv
+import json
+import os
+import re
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+# kernel name fragment -> C-ABI call it belongs to (scatter_rows serves two calls: see _call_of)
+_KERNEL_CALL = [
+    ("route_mfma", "moga_route"), ("route_generic", "moga_route"),
+    ("chunk_hist", "moga_permute"), ("chunk_scan", "moga_permute"), ("chunk_rank", "moga_permute"),
+    ("gather_rows_kernel", "moga_permute"),
+    ("attn_fwd", "moga_group_attn_fwd"),
+    ("unpermute_bwd", "moga_unpermute_bwd"),
+    ("attn_bwd", "moga_group_attn_bwd"),
+    ("route_bwd", "moga_route_bwd"),
+]
+
+
+def short_name(kernel: str) -> str:
+    return kernel.split("(")[0].replace("void ", "").strip()
+
+
+def read_kernel_stats(path):
+    """rocprofv3 --stats kernel summary -> {kernel: dict(calls, avg_ms, total_ms, pct)}"""
+    out = {}
+    for r in csv.DictReader(open(path)):
+        out[short_name(r["Name"])] = {"calls": int(r["Calls"]), "avg_ms": float(r["AverageNs"]) / 1e6,
+                                      "total_ms": float(r["TotalDurationNs"]) / 1e6, "pct": float(r["Percentage"])}
+    return out
+
+
+def read_counters(path):
+    """rocprofv3 --pmc counter_collection.csv -> {kernel: {counter: [value per dispatch, in dispatch order]}}"""
+    rows = list(csv.DictReader(open(path)))
+    rows.sort(key=lambda r: int(r.get("Dispatch_Id", 0)))
+    out = collections.defaultdict(lambda: collections.defaultdict(list))
+    for r in rows:
+        out[short_name(r["Kernel_Name"])][r["Counter_Name"]].append(float(r["Counter_Value"]))
+    return out
+
+
+def _call_of(kernel: str, nth_dispatch: int):
+    if "scatter_rows_kernel" in kernel:      # first launch of a step: moga_unpermute; second: moga_permute_bwd
+        return "moga_unpermute" if nth_dispatch % 2 == 0 else "moga_permute_bwd"
+    for frag, call in _KERNEL_CALL:
+        if frag in kernel:
+            return call
+    return None
+
+
+def _bench_line(path):
+    for l in open(path):
+        if l.startswith("{"):
+            return json.loads(l)
+    raise RuntimeError(f"no JSON line in {path}")
+
+
+def traffic_path(workload: str) -> str:
+    return os.path.join(ROOT, "profiles", f"layer_{workload}_hbm_traffic.md")
+
+
+def read_call_traffic(workload: str):
+    """{C-ABI call: HBM bytes per call} from the tracked traffic summary of `workload` ({} if there is none)."""
+    path = traffic_path(workload)
+    if not os.path.exists(path):
+        return {}
+    out = {}
+    for l in open(path):
+        m = re.match(r"\|\s*(moga_[a-z_]+)\s*\|\s*([0-9.]+)\s*GB\s*\|", l)
+        if m:
+            out[m.group(1)] = float(m.group(2)) * 1e9
+    return out
+
+
+def write_layer(args):
+    stats = read_kernel_stats(args.stats)
+    F, W = read_counters(args.fetch), read_counters(args.write)
+    line = _bench_line(args.bench_log)
+    wl = args.workload
+    cal_f = [v for k, d in F.items() if "copy_kernel" in k for v in d["FETCH_SIZE"]]
+    cal_w = [v for k, d in W.items() if "copy_kernel" in k for v in d["WRITE_SIZE"]]
+    gib_kib = float(1 << 20)
+    ff = gib_kib / cal_f[0] if cal_f else 2.0
+    fw = gib_kib / cal_w[0] if cal_w else 1.0
+    per_call = collections.defaultdict(float)
+    rows = []
+    for k in sorted(F, key=lambda k: -sum(F[k]["FETCH_SIZE"])):
+        if "moga::" not in k:
+            continue
+        fs, ws = F[k]["FETCH_SIZE"], W.get(k, {}).get("WRITE_SIZE", [])
+        for i, f in enumerate(fs):
+            w_ = ws[i] if i < len(ws) else 0.0
+            rd, wr = f * ff * 1024, w_ * fw * 1024
+            call = _call_of(k, i)
+            if call:
+                per_call[call] += (rd + wr) / max(1, len(fs) // (2 if "scatter_rows" in k else 1))
+            rows.append(f"| {k} #{i} | {f:,.0f} | {w_:,.0f} | {rd / 1e9:.2f} | {wr / 1e9:.2f} |")
+    calls = line.get("calls", {})
+    ctab = []
+    for c, b in per_call.items():
+        ms = calls.get(c, {}).get("ms")
+        rate = f"{b / ms / 1e6:.0f} GB/s over {ms:.2f} ms" if ms else "-"
+        ctab.append(f"| {c} | {b / 1e9:.2f} GB | {rate} |")
+    cmd = ("rocprofv3 --pmc {c} --kernel-trace -d gpurun_out/pmc_{n} -o {n} --output-format csv -- "
+           f"python3 bench.py --workload {wl} --steps 1 --warmup 0 --no-cpu-baseline --calibrate-copy")
+    txt = f"""# HBM traffic per kernel launch (rocprofv3 PMC), workload {wl}
+
+Commands (one counter per run, from the repository root on one MI355X):
+
+    {cmd.format(c="FETCH_SIZE", n="fetch")}
+    {cmd.format(c="WRITE_SIZE", n="write")}
+    python -m paper_2510_18692_amd.profiling layer --workload {wl} ...   (writes this file)
+
+Calibration: `--calibrate-copy` runs the library's plain copy kernel on 1 GiB (1,048,576 KiB read, the same written).
+For that copy FETCH_SIZE reads {cal_f[0] if cal_f else float('nan'):,.0f} KiB (factor {ff:.2f}) and WRITE_SIZE reads {cal_w[0] if cal_w else float('nan'):,.0f} KiB (factor {fw:.2f}).
+Columns: raw counters in KiB per dispatch, then bytes scaled by those factors.  `#i` is the i-th launch of the kernel
+in the step (scatter_rows_kernel: #0 is moga_unpermute, #1 is moga_permute_bwd).
+
+| kernel launch | FETCH_SIZE KiB | WRITE_SIZE KiB | HBM read GB | HBM written GB |
+|---|---|---|---|---|
+""" + "\n".join(rows) + """
+
+Per C-ABI call (bench.py reads this table for `roofline.traffic`; rates use the HIP-event time of the same run):
+
+| call | HBM bytes | rate |
+|---|---|---|
+""" + "\n".join(ctab) + "\n"
+    open(os.path.join(args.out_dir, f"layer_{wl}_hbm_traffic.md"), "w").write(txt)
+    krows = [f"| {k} | {v['calls']} | {v['avg_ms']:.3f} | {v['total_ms']:.2f} | {v['pct']:.3f} |"
+             for k, v in sorted(stats.items(), key=lambda kv: -kv[1]["total_ms"]) if "moga::" in k]
+    clines = "\n".join(f"- {k}: {v['ms']} ms, {v['achieved']} {v['unit']} ({100 * v['frac']:.1f} % of {v['peak']} {v['unit']})"
+                       for k, v in calls.items())
+    steps = line.get("steps", 0) + line.get("warmup", 0)
+    txt = f"""# rocprofv3 kernel stats: whole MoGA layer, workload {wl}
+
+{line['config']['workload']}
+
+Command (run from the repository root on one MI355X):
+
+    rocprofv3 --kernel-trace --stats -d gpurun_out/prof_{wl} -o {wl} --output-format csv -- python3 bench.py --workload {wl} --steps {line.get('steps')} --warmup {line.get('warmup')} --no-cpu-baseline
+
+{steps} launches of every kernel per step count.  Library kernels only (torch's input-generation kernels omitted):
+
+| kernel | calls | avg ms | total ms | % of GPU time |
+|---|---|---|---|---|
+""" + "\n".join(krows) + f"""
+
+bench.py line of the same run (HIP-event timing per C-ABI call):
+
+{clines}
+- whole step: {line['ms_per_step']} ms, {line['value']} effective TFLOP/s
+- measured peaks of the same run: {json.dumps(line.get('roofline', {}).get('measured_peak'))}
+"""
+    open(os.path.join(args.out_dir, f"layer_{wl}_kernel_stats.md"), "w").write(txt)
+    print(txt)
+
+
+def write_counters(args):
+    stats = read_kernel_stats(args.stats) if args.stats else {}
+    merged = collections.defaultdict(dict)
+    for path in args.csv:
+        for k, d in read_counters(path).items():
+            for c, vals in d.items():
+                merged[k][c] = sum(vals) / len(vals)
+    want = [k for k in merged if any(s in k for s in ("attn_fwd_bf16", "attn_bwd_dkdv", "attn_bwd_dq", "route_mfma",
+                                                      "route_bwd_dw_mfma"))]
+    names = sorted({c for k in want for c in merged[k]})
+    hdr = "| kernel | " + " | ".join(names) + " |\n|---|" + "---|" * len(names)
+    rows = ["| " + k + " | " + " | ".join(f"{merged[k].get(c, float('nan')):,.0f}" for c in names) + " |" for k in want]
+    derived = []
+    for k in want:
+        m = merged[k]
+        parts = [k + ":"]
+        if "SQ_BUSY_CU_CYCLES" in m and "SQ_VALU_MFMA_BUSY_CYCLES" in m and m["SQ_BUSY_CU_CYCLES"] > 0:
+            parts.append(f"MFMA busy / CU busy = {m['SQ_VALU_MFMA_BUSY_CYCLES'] / m['SQ_BUSY_CU_CYCLES']:.3f}")
+        if "GRBM_GUI_ACTIVE" in m and k in stats:
+            parts.append(f"clock = GRBM_GUI_ACTIVE / kernel time = {m['GRBM_GUI_ACTIVE'] / (stats[k]['avg_ms'] * 1e-3) / 1e9:.2f} GHz")
+        if "SQ_INSTS_VALU_MFMA_MOPS_BF16" in m and k in stats:
+            tf = m["SQ_INSTS_VALU_MFMA_MOPS_BF16"] * 512 / (stats[k]["avg_ms"] * 1e-3) / 1e12
+            parts.append(f"executed MFMA rate = MOPS x 512 FLOP / kernel time = {tf:.0f} TFLOP/s ({tf / 2500:.3f} of the published peak)")
+        if "SQ_WAVE_CYCLES" in m and "SQ_WAIT_INST_LDS" in m and m["SQ_WAVE_CYCLES"] > 0:
+            parts.append(f"waiting for LDS = {m['SQ_WAIT_INST_LDS'] / m['SQ_WAVE_CYCLES']:.3f} of wave cycles")
+        if "SQ_LDS_BANK_CONFLICT" in m and "SQ_LDS_IDX_ACTIVE" in m and m["SQ_LDS_IDX_ACTIVE"] > 0:
+            parts.append(f"LDS bank-conflict cycles / LDS active cycles = {m['SQ_LDS_BANK_CONFLICT'] / m['SQ_LDS_IDX_ACTIVE']:.4f}")
+        derived.append("- " + " ".join(parts))
+    txt = f"""# MFMA and LDS counters of the matrix-core kernels (rocprofv3 PMC), workload {args.workload}
+
+Commands (one run per counter set, each `timeout -s KILL 300 rocprofv3 --pmc <set> --kernel-trace -d gpurun_out/<dir>
+-o <name> --output-format csv -- python3 bench.py --workload {args.workload} --steps 1 --warmup 0 --no-cpu-baseline`):
+
+""" + "\n".join(f"    set {i + 1}: {os.path.basename(os.path.dirname(p))}: " + " ".join(sorted(
+        {c for d in read_counters(p).values() for c in d})) for i, p in enumerate(args.csv)) + f"""
+
+    python -m paper_2510_18692_amd.profiling counters --workload {args.workload} ...   (writes this file)
+
+Kernel times come from the `--kernel-trace --stats` run summarised in layer_{args.workload}_kernel_stats.md.
+Counter values are per dispatch (mean over the dispatches of the run), summed over all XCDs / shader engines as
+rocprofv3 reports them.
+
+{hdr}
+""" + "\n".join(rows) + "\n\nDerived:\n\n" + "\n".join(derived) + "\n"
+    open(args.out, "w").write(txt)
+    print(txt)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    sub = ap.add_subparsers(dest="cmd", required=True)
+    a = sub.add_parser("layer")
+    a.add_argument("--workload", default="C4b")
+    a.add_argument("--stats", required=True)
+    a.add_argument("--fetch", required=True)
+    a.add_argument("--write", required=True)
+    a.add_argument("--bench-log", required=True)
+    a.add_argument("--out-dir", default=os.path.join(ROOT, "profiles"))
+    a.set_defaults(fn=write_layer)
+    b = sub.add_parser("counters")
+    b.add_argument("--workload", default="C4b")
+    b.add_argument("--stats")
+    b.add_argument("--csv", nargs="+", required=True)
+    b.add_argument("--out", required=True)
+    b.set_defaults(fn=write_counters)
+    args = ap.parse_args()
+    args.fn(args)
+
+
+if __name__ == "__main__":
+    main()
