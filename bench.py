@@ -49,6 +49,9 @@ def parse():
     ap.add_argument("--window", default="8x13x0",
                     help="--block: spatial window rows x cols x frames per run (0 = a whole shot). The default is the "
                          "4 x 4 partition of the 30 x 52 latent frame that the paper pairs with long contexts")
+    ap.add_argument("--small-group-rows", type=int, default=-1,
+                    help="override the mean group size below which the bf16 attention calls use their small-group "
+                         "kernels (0: never; default -1: the library's own thresholds)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-measured-peaks", action="store_true",
                     help="skip the two peak microbenchmarks (register-resident MFMA loop, plain 1 GiB copy)")
@@ -246,9 +249,11 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    mg.load()
+    if args.small_group_rows >= 0:
+        mg.set_small_group_rows(args.small_group_rows)
     if args.block:
         return run_block(args)
-    mg.load()
     w = wl.WORKLOADS[args.workload]
     torch.cuda.set_device(0)
     inp = wl.make_inputs(w, "cuda")

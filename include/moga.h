@@ -174,6 +174,16 @@ int moga_group_attn_bwd(const void* d_oh, const void* qh, const void* kh, const 
 size_t moga_attn_bwd_status_offset(int64_t Nq, int H);
 void moga_debug_set_spin_limit(int polls);
 
+/*
+ * The BF16 attention calls have two sets of kernels: 8-wave blocks with 256-row (forward, dQ) or
+ * 128-row (dK/dV) tiles, and 4-wave blocks with tiles half as large, two blocks per CU, for the small
+ * static groups of Section 3.2.  The group sizes live on the device, so a call chooses by the mean
+ * group size N / M (forward: below 2560 rows; backward: below 1280).  Both sets give the same results up
+ * to rounding order.  moga_debug_set_small_group_rows overrides both thresholds (0: never the small
+ * kernels; a huge value: always; negative: the defaults) so that tests can run either set on any shape.
+ */
+void moga_debug_set_small_group_rows(int64_t rows);
+
 /* Backward of the gather in moga_permute: d_q[perm[j]][h][:] = d_qh[h][j][:] (same for k, v). */
 int moga_permute_bwd(const void* d_qh, const void* d_kh, const void* d_vh, int dtype,
                      const int32_t* perm, int64_t N, int H, int D,

@@ -39,6 +39,7 @@ _SIGNATURES = {
                                    _f32, _vp, _vp, _vp, _vp, _sz, _vp]),
     "moga_attn_bwd_status_offset": (_sz, [_i64, _i32]),
     "moga_debug_set_spin_limit": (None, [_i32]),
+    "moga_debug_set_small_group_rows": (None, [_i64]),
     "moga_permute_bwd": (_i32, [_vp, _vp, _vp, _i32, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp]),
     "moga_route_bwd": (_i32, [_vp, _i32, _vp, _vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _vp, _vp,
                               _sz, _vp]),
@@ -223,6 +224,11 @@ def attn_bwd_status(ws, Nq, H):
     """The int32 status word of a backward workspace (0 after every correct run), as a 1-element view."""
     off = int(load().moga_attn_bwd_status_offset(Nq, H))
     return ws[off:off + 4].view(torch.int32)
+
+
+def set_small_group_rows(rows: int) -> None:
+    """Mean group size below which the bf16 attention calls use their small-group kernels (< 0: defaults)."""
+    load().moga_debug_set_small_group_rows(int(rows))
 
 
 def set_spin_limit(polls: int) -> None:

@@ -1,4 +1,6 @@
 // Host-only entry points of the C ABI: status strings, version, workspace sizes.
+#include <atomic>
+
 #include "moga_common.h"
 
 extern "C" size_t moga_permute_ws_bytes(int64_t N, int M);
@@ -19,7 +21,18 @@ extern "C" const char* moga_status_string(int status) {
   }
 }
 
-extern "C" int moga_version(void) { return 103; }
+extern "C" int moga_version(void) { return 104; }
+
+// Test hook: overrides the mean group size below which the bf16 attention calls pick their
+// small-group kernels (negative: each call's own default).
+static std::atomic<long long> g_small_group_rows{-1};
+extern "C" void moga_debug_set_small_group_rows(int64_t rows) { g_small_group_rows.store(rows); }
+namespace moga {
+bool use_small_group_kernels(int64_t rows, int groups, int64_t default_threshold) {
+  const long long o = g_small_group_rows.load();
+  return rows / (groups > 0 ? groups : 1) < (o >= 0 ? o : default_threshold);
+}
+}  // namespace moga
 
 extern "C" size_t moga_workspace_bytes(int op, int64_t N, int H, int D, int M, int d_model,
                                        int dtype) {

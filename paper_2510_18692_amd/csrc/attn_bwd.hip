@@ -123,6 +123,8 @@ __global__ __launch_bounds__(256) void attn_bwd_fused_prepass_kernel(
 // fp32 (head_dim 64): one thread per row
 // ---------------------------------------------------------------------------------------
 constexpr int kF32BM = 64, kF32BN = 32;
+constexpr int64_t kSmallGroupRows = 1280;   // mean rows per group below which the small-group bf16 kernels run
+                                            // (398 against 334 TFLOP/s at 312 rows, equal at 1,560, slower above)
 
 template <int D>
 __global__ __launch_bounds__(64) void attn_bwd_dq_f32_kernel(
@@ -294,25 +296,42 @@ static int launch_attn_bwd(const void* d_oh, const void* qh, const void* kh, con
     int* status = (int*)((char*)delta + bwd_rows_bytes(Nq, H));
     attn_bwd_delta_kernel<16, true><<<(unsigned)((rows * 16 + 255) / 256), 256, 0, st>>>(
         (const uintx4_t*)d_oh, (const uintx4_t*)oh, lse, rows, 1.f / softmax_scale, delta, lse2, status);
+    // groups of a few thousand rows or less (the static groups of Section 3.2): 4-wave blocks with a
+    // two-slot ring, two blocks per CU, and tiles half as large; the host only knows the mean group size
+    const bool small = use_small_group_kernels(Nq, M, kSmallGroupRows);
     if (Nk > 0) {
-      const int64_t tiles = max_tiles(Nk, M, 128);
+      const int bk = small ? 64 : 128;
+      const int64_t tiles = max_tiles(Nk, M, bk);
       const int64_t blocks = (tiles * H + 7) / 8 * 8;
       if (blocks >= ((int64_t)1 << 31)) return MOGA_ERR_UNSUPPORTED;
-      if (ts_k) tile_start_kernel<<<1, 1024, 0, st>>>(cu_k, M, 128, ts_k);
-      attn_bwd_dkdv_ab_kernel<false><<<(unsigned)blocks, 512, 0, st>>>(
-          (const unsigned short*)d_oh, (const unsigned short*)qh, (const unsigned short*)kh,
-          (const unsigned short*)vh, lse2, delta, cu_q, cu_k, ts_k, M, Nq, Nk, H, softmax_scale,
-          (int)tiles, (unsigned short*)d_kh, (unsigned short*)d_vh, g_spin_limit.load(), status);
+      if (ts_k) tile_start_kernel<<<1, 1024, 0, st>>>(cu_k, M, bk, ts_k);
+      if (small)
+        attn_bwd_dkdv_ab_kernel<false, 2, 2><<<(unsigned)blocks, 256, 0, st>>>(
+            (const unsigned short*)d_oh, (const unsigned short*)qh, (const unsigned short*)kh,
+            (const unsigned short*)vh, lse2, delta, cu_q, cu_k, ts_k, M, Nq, Nk, H, softmax_scale,
+            (int)tiles, (unsigned short*)d_kh, (unsigned short*)d_vh, g_spin_limit.load(), status);
+      else
+        attn_bwd_dkdv_ab_kernel<false><<<(unsigned)blocks, 512, 0, st>>>(
+            (const unsigned short*)d_oh, (const unsigned short*)qh, (const unsigned short*)kh,
+            (const unsigned short*)vh, lse2, delta, cu_q, cu_k, ts_k, M, Nq, Nk, H, softmax_scale,
+            (int)tiles, (unsigned short*)d_kh, (unsigned short*)d_vh, g_spin_limit.load(), status);
     }
     {
-      const int64_t tiles = max_tiles(Nq, M, 256);
+      const int bm = small ? 128 : 256;
+      const int64_t tiles = max_tiles(Nq, M, bm);
       const int64_t blocks = (tiles * H + 7) / 8 * 8;
       if (blocks >= ((int64_t)1 << 31)) return MOGA_ERR_UNSUPPORTED;
-      if (ts_q) tile_start_kernel<<<1, 1024, 0, st>>>(cu_q, M, 256, ts_q);
-      attn_bwd_dq_pipe_kernel<8, 1><<<(unsigned)blocks, 512, 0, st>>>(
-          (const unsigned short*)d_oh, (const unsigned short*)qh, (const unsigned short*)kh,
-          (const unsigned short*)vh, lse2, delta, cu_q, cu_k, ts_q, M, Nq, Nk, H, softmax_scale,
-          (int)tiles, (unsigned short*)d_qh);
+      if (ts_q) tile_start_kernel<<<1, 1024, 0, st>>>(cu_q, M, bm, ts_q);
+      if (small)
+        attn_bwd_dq_pipe_kernel<4, 1, false, 2><<<(unsigned)blocks, 256, 0, st>>>(
+            (const unsigned short*)d_oh, (const unsigned short*)qh, (const unsigned short*)kh,
+            (const unsigned short*)vh, lse2, delta, cu_q, cu_k, ts_q, M, Nq, Nk, H, softmax_scale,
+            (int)tiles, (unsigned short*)d_qh);
+      else
+        attn_bwd_dq_pipe_kernel<8, 1><<<(unsigned)blocks, 512, 0, st>>>(
+            (const unsigned short*)d_oh, (const unsigned short*)qh, (const unsigned short*)kh,
+            (const unsigned short*)vh, lse2, delta, cu_q, cu_k, ts_q, M, Nq, Nk, H, softmax_scale,
+            (int)tiles, (unsigned short*)d_qh);
     }
   } else {
     if (D == 64)

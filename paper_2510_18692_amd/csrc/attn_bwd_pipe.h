@@ -7,7 +7,8 @@
 //                               tiles of Q, dO, lse and delta; one wave computes S, P and dV^T,
 //                               the other dP, dS and dK^T (P handed over through LDS).
 // Tiles are streamed global -> LDS by direct-to-LDS loads into a ring of four slots, two tiles
-// ahead; one block-wide barrier per tile.
+// ahead; one block-wide barrier per tile.  Both kernels also come as 4-wave blocks with a two-slot
+// ring (64 KB of LDS), two blocks per CU, for groups of a few thousand rows or less.
 #pragma once
 
 #include "attn_pipe.h"
@@ -126,8 +127,10 @@ __device__ __forceinline__ void dq_tile(const DqLane& ln, unsigned off, const bf
 // [N, H, 128] and row j of a group is token perm[j]; neg_lse_over_scale / neg_delta stay in
 // sorted order [H, N] and carry the gate (see attn_bwd_fused_prepass_kernel), so d_oh is the
 // raw upstream gradient of the gated output.
-template <int NW, int QW, bool GATHER = false>
-__global__ __launch_bounds__(NW * 64) void attn_bwd_dq_pipe_kernel(
+// NB: ring slots of 64 keys (4: two tiles ahead, one block per CU; 2: one tile ahead, 64 KB of LDS, so
+// that two 4-wave blocks share a CU -- the variant for small groups).
+template <int NW, int QW, bool GATHER = false, int NB = 4>
+__global__ __launch_bounds__(NW * 64, NB == 2 ? 2 : 1) void attn_bwd_dq_pipe_kernel(
     const unsigned short* __restrict__ d_oh, const unsigned short* __restrict__ qh,
     const unsigned short* __restrict__ kh, const unsigned short* __restrict__ vh,
     const float* __restrict__ neg_lse_over_scale, const float* __restrict__ neg_delta,
@@ -136,8 +139,9 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_pipe_kernel(
     int tiles_per_head, unsigned short* __restrict__ d_qh, const int32_t* __restrict__ perm = nullptr) {
   constexpr int BM = NW * 32 * QW;
   constexpr int kDmaPerTile = 2 * (16 / NW);
-  __shared__ __attribute__((aligned(1024))) unsigned short Ks[kPipeNBuf][64 * kHeadDim];
-  __shared__ __attribute__((aligned(1024))) unsigned short Vs[kPipeNBuf][64 * kHeadDim];
+  constexpr int kAhead = NB - 2;   // tiles in flight beyond the one being waited for
+  __shared__ __attribute__((aligned(1024))) unsigned short Ks[NB][64 * kHeadDim];
+  __shared__ __attribute__((aligned(1024))) unsigned short Vs[NB][64 * kHeadDim];
   __shared__ int s_start[MOGA_MAX_GROUPS + 1];
   __shared__ int s_found;
 
@@ -211,7 +215,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_pipe_kernel(
     pipe_load_tokens<NW>(dma, 0);
   }
 #pragma unroll
-  for (int t = 0; t <= kPipeAhead; ++t) pipe_issue<NW, GATHER>(dma, 64 * t, t);
+  for (int t = 0; t <= kAhead; ++t) pipe_issue<NW, GATHER>(dma, 64 * t, t);
 
   DqLane ln;
   {
@@ -247,10 +251,10 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_pipe_kernel(
   const int nfull = n >> 6;   // tiles whose 64 keys are all inside the group
   int T = 0;
 #define MOGA_DQ_TILE(B)                                                                  \
-  __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * kPipeAhead));                      \
+  __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * kAhead));                      \
   __syncthreads();                                                                       \
-  pipe_issue<NW, GATHER>(dma, 64 * (T + (B) + 1 + kPipeAhead), ((B) + 1 + kPipeAhead) & 3); \
-  dq_tile<QW, false, (B) * kPipeTileBytes>(ln, 0, qf, dof, lq, dl, dq, c, h, 64);
+  pipe_issue<NW, GATHER>(dma, 64 * (T + (B) + 1 + kAhead), ((B) + 1 + kAhead) & (NB - 1)); \
+  dq_tile<QW, false, ((B) & (NB - 1)) * kPipeTileBytes>(ln, 0, qf, dof, lq, dl, dq, c, h, 64);
   for (; T + 4 <= nfull; T += 4) {   // four tiles per iteration: every LDS offset is an immediate
     MOGA_DQ_TILE(0)
     MOGA_DQ_TILE(1)
@@ -259,15 +263,15 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_pipe_kernel(
   }
 #undef MOGA_DQ_TILE
   for (; T < nfull; ++T) {
-    __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * kPipeAhead));
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * kAhead));
     __syncthreads();
-    pipe_issue<NW, GATHER>(dma, 64 * (T + 1 + kPipeAhead), (T + 1 + kPipeAhead) & 3);
-    dq_tile<QW, false, 0>(ln, ((unsigned)T & 3u) * kPipeTileBytes, qf, dof, lq, dl, dq, c, h, 64);
+    pipe_issue<NW, GATHER>(dma, 64 * (T + 1 + kAhead), (T + 1 + kAhead) & (NB - 1));
+    dq_tile<QW, false, 0>(ln, ((unsigned)T & (unsigned)(NB - 1)) * kPipeTileBytes, qf, dof, lq, dl, dq, c, h, 64);
   }
   if (n & 63) {   // last, partial tile: masked keys contribute zero
-    __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * kPipeAhead));
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * kAhead));
     __syncthreads();
-    dq_tile<QW, true, 0>(ln, ((unsigned)T & 3u) * kPipeTileBytes, qf, dof, lq, dl, dq, c, h, n - 64 * T);
+    dq_tile<QW, true, 0>(ln, ((unsigned)T & (unsigned)(NB - 1)) * kPipeTileBytes, qf, dof, lq, dl, dq, c, h, n - 64 * T);
   }
 
   __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // drain the look-ahead loads before the LDS is released
@@ -432,8 +436,10 @@ __device__ __forceinline__ void ab_tile(const AbLane& ln, int role, unsigned off
   ab_accumulate(tr1, bop[1], acc);
 }
 
-template <bool GATHER = false>
-__global__ __launch_bounds__(512) void attn_bwd_dkdv_ab_kernel(
+// NPAIR: wave pairs per block (4: 128 keys, partners on one SIMD; 2: 64 keys, for small groups).
+// NB: ring slots of 64 queries (4 or 2, as in the dQ kernel).
+template <bool GATHER = false, int NPAIR = 4, int NB = 4>
+__global__ __launch_bounds__(NPAIR * 128, NB == 2 ? 2 : 1) void attn_bwd_dkdv_ab_kernel(
     const unsigned short* __restrict__ d_oh, const unsigned short* __restrict__ qh,
     const unsigned short* __restrict__ kh, const unsigned short* __restrict__ vh,
     const float* __restrict__ neg_lse_over_scale, const float* __restrict__ neg_delta,
@@ -441,15 +447,16 @@ __global__ __launch_bounds__(512) void attn_bwd_dkdv_ab_kernel(
     const int32_t* __restrict__ tile_start, int M, int64_t Nq, int64_t Nk, int H, float scale,
     int tiles_per_head, unsigned short* __restrict__ d_kh, unsigned short* __restrict__ d_vh,
     int spin_limit, int* __restrict__ status, const int32_t* __restrict__ perm = nullptr) {
-  constexpr int NW = 8;
-  constexpr int BK = 128;                          // 4 pairs of waves x 32 keys
+  constexpr int NW = 2 * NPAIR;
+  constexpr int BK = 32 * NPAIR;                   // pairs of waves x 32 keys
+  constexpr int kAhead = NB - 2;
   constexpr int kDmaPerTile = 2 * (16 / NW) + 2;
-  __shared__ __attribute__((aligned(1024))) unsigned short Qs[kPipeNBuf][64 * kHeadDim];
-  __shared__ __attribute__((aligned(1024))) unsigned short dOs[kPipeNBuf][64 * kHeadDim];
-  __shared__ __attribute__((aligned(1024))) unsigned char Ps[4][4096];   // P of one tile, per pair
-  __shared__ __attribute__((aligned(256))) float Ls[kPipeNBuf][64];      // -lse / scale
-  __shared__ __attribute__((aligned(256))) float Ds[kPipeNBuf][64];      // -delta
-  __shared__ int s_flag[4];   // per pair: number of tiles whose P has been written
+  __shared__ __attribute__((aligned(1024))) unsigned short Qs[NB][64 * kHeadDim];
+  __shared__ __attribute__((aligned(1024))) unsigned short dOs[NB][64 * kHeadDim];
+  __shared__ __attribute__((aligned(1024))) unsigned char Ps[NPAIR][4096];   // P of one tile, per pair
+  __shared__ __attribute__((aligned(256))) float Ls[NB][64];      // -lse / scale
+  __shared__ __attribute__((aligned(256))) float Ds[NB][64];      // -delta
+  __shared__ int s_flag[NPAIR];   // per pair: number of tiles whose P has been written
   __shared__ int s_start[MOGA_MAX_GROUPS + 1];
   __shared__ int s_found;
 
@@ -458,7 +465,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dkdv_ab_kernel(
   if (work >= total) return;
   const int head = (int)(work / tiles_per_head);
   const int tile = (int)(work - (int64_t)head * tiles_per_head);
-  if (threadIdx.x < 4) s_flag[threadIdx.x] = 0;   // ordered before its first use by the barriers below
+  if (threadIdx.x < NPAIR) s_flag[threadIdx.x] = 0;   // ordered before its first use by the barriers below
   TileInfo ti;   // tiles run over the key rows of the groups
   if (tile_start) {
     if (!find_tile_presummed(tile_start, cu_k, M, BK, tile, ti)) return;
@@ -470,7 +477,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dkdv_ab_kernel(
   const int n = cu_q[ti.group + 1] - gs;
 
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-  const int role = wave >> 2, pair = wave & 3;
+  const int role = wave / NPAIR, pair = wave % NPAIR;
   int* flag = &s_flag[pair];
   const int r = lane & 31, h = lane >> 5;
   const int64_t head_off = (int64_t)head * Nk;
@@ -519,14 +526,14 @@ __global__ __launch_bounds__(512) void attn_bwd_dkdv_ab_kernel(
   const void* dbase = uniform_ptr(neg_delta + head_off_q + gs);
   const unsigned lds_l = lds_addr_uniform(&Ls[0][0]), lds_d = lds_addr_uniform(&Ds[0][0]);
   auto issue_tile = [&](int T) {   // every wave issues the (identical) row-constant loads so that all count alike
-    const int slot = T & 3;
+    const int slot = T & (NB - 1);
     pipe_issue<NW, GATHER>(dma, 64 * T, slot);
     const unsigned roff = (unsigned)min(64 * T + lane, n - 1) * 4u;
     lds_dma4_soff(lbase, roff, lds_l + slot * 256);
     lds_dma4_soff(dbase, roff, lds_d + slot * 256);
   };
 #pragma unroll
-  for (int t = 0; t <= kPipeAhead; ++t) issue_tile(t);
+  for (int t = 0; t <= kAhead; ++t) issue_tile(t);
 
   AbLane ln;
   {
@@ -557,10 +564,10 @@ __global__ __launch_bounds__(512) void attn_bwd_dkdv_ab_kernel(
   const int nfull = n >> 6;   // tiles whose 64 queries are all inside the group
   int T = 0;
 #define MOGA_AB_TILE(B)                                                          \
-  __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * kPipeAhead));              \
+  __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * kAhead));              \
   __syncthreads();                                                               \
-  issue_tile(T + (B) + 1 + kPipeAhead);                                          \
-  ab_tile<false, (B) * kPipeTileBytes, (B) * 256>(ln, role, 0, 0, kvf, acc, c, h, 64, flag, T + (B) + 1, \
+  issue_tile(T + (B) + 1 + kAhead);                                          \
+  ab_tile<false, ((B) & (NB - 1)) * kPipeTileBytes, ((B) & (NB - 1)) * 256>(ln, role, 0, 0, kvf, acc, c, h, 64, flag, T + (B) + 1, \
                                                   spin_limit, status);
   for (; T + 4 <= nfull; T += 4) {   // four tiles per iteration: every LDS offset is an immediate
     MOGA_AB_TILE(0)
@@ -570,16 +577,16 @@ __global__ __launch_bounds__(512) void attn_bwd_dkdv_ab_kernel(
   }
 #undef MOGA_AB_TILE
   for (; T < nfull; ++T) {
-    __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * kPipeAhead));
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * kAhead));
     __syncthreads();
-    issue_tile(T + 1 + kPipeAhead);
-    ab_tile<false, 0, 0>(ln, role, ((unsigned)T & 3u) * kPipeTileBytes, ((unsigned)T & 3u) * 256, kvf, acc, c, h, 64,
+    issue_tile(T + 1 + kAhead);
+    ab_tile<false, 0, 0>(ln, role, ((unsigned)T & (unsigned)(NB - 1)) * kPipeTileBytes, ((unsigned)T & (unsigned)(NB - 1)) * 256, kvf, acc, c, h, 64,
                          flag, T + 1, spin_limit, status);
   }
   if (n & 63) {   // last, partial tile: masked queries get P = 0 and contribute nothing
-    __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * kPipeAhead));
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * kAhead));
     __syncthreads();
-    ab_tile<true, 0, 0>(ln, role, ((unsigned)T & 3u) * kPipeTileBytes, ((unsigned)T & 3u) * 256, kvf, acc, c, h,
+    ab_tile<true, 0, 0>(ln, role, ((unsigned)T & (unsigned)(NB - 1)) * kPipeTileBytes, ((unsigned)T & (unsigned)(NB - 1)) * 256, kvf, acc, c, h,
                         n - 64 * T, flag, T + 1, spin_limit, status);
   }
 

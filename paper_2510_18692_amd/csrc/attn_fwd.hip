@@ -12,6 +12,7 @@
 // fp32 kernel: one thread per query row, plain FMA, for the full-precision configuration.
 #include "attn_common.h"
 #include "attn_pipe.h"
+#include "attn_pipe_small.h"
 
 namespace moga {
 
@@ -19,6 +20,8 @@ namespace moga {
 // fp32: one thread per query row
 // ---------------------------------------------------------------------------------------
 constexpr int kF32BM = 64, kF32BN = 32;
+constexpr int64_t kSmallGroupRows = 2560;   // mean rows per group below which the small-group bf16 kernel runs
+                                            // (927 against 886 TFLOP/s at 1,560 rows, 1052 against 1063 at 3,224)
 
 template <int D>
 __global__ __launch_bounds__(64) void attn_fwd_f32_kernel(
@@ -126,12 +129,19 @@ static int launch_attn_fwd(const void* qh, const void* kh, const void* vh, int d
                            int64_t Nk, int H, int D, const int32_t* cu_q, const int32_t* cu_k,
                            int32_t* tile_start, int M, float softmax_scale, void* oh, float* lse,
                            hipStream_t st) {
-  const int bm = dtype == MOGA_BF16 ? 256 : kF32BM;
+  // bf16: groups of a few thousand rows or less (the static groups of Section 3.2) take the kernel
+  // with 128-row tiles and two 4-wave blocks per CU; the host only knows the mean group size
+  const bool small = dtype == MOGA_BF16 && use_small_group_kernels(Nq, M, kSmallGroupRows);
+  const int bm = dtype == MOGA_BF16 ? (small ? 128 : 256) : kF32BM;
   const int64_t tiles = max_tiles(Nq, M, bm);
   const int64_t blocks = dtype == MOGA_BF16 ? (tiles * H + 7) / 8 * 8 : tiles * H;
   if (blocks >= ((int64_t)1 << 31)) return MOGA_ERR_UNSUPPORTED;
   if (tile_start) tile_start_kernel<<<1, 1024, 0, st>>>(cu_q, M, bm, tile_start);
-  if (dtype == MOGA_BF16) {
+  if (small) {
+    attn_fwd_bf16_small_kernel<<<(unsigned)blocks, 256, 0, st>>>(
+        (const unsigned short*)qh, (const unsigned short*)kh, (const unsigned short*)vh, cu_q, cu_k,
+        tile_start, M, Nq, Nk, H, softmax_scale, (int)tiles, (unsigned short*)oh, lse);
+  } else if (dtype == MOGA_BF16) {
     attn_fwd_bf16_pipe_kernel<8, 1><<<(unsigned)blocks, 512, 0, st>>>(
         (const unsigned short*)qh, (const unsigned short*)kh, (const unsigned short*)vh, cu_q, cu_k,
         tile_start, M, Nq, Nk, H, softmax_scale, (int)tiles, (unsigned short*)oh, lse);

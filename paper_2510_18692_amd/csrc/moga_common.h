@@ -71,6 +71,8 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 }
 
 // ---- host side ------------------------------------------------------------
+// true when groups of mean size rows / groups should run on the small-group bf16 attention kernels
+bool use_small_group_kernels(int64_t rows, int groups, int64_t default_threshold);
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline int launch_status() { return hipGetLastError() == hipSuccess ? MOGA_OK : MOGA_ERR_HIP; }
 inline size_t round_up(size_t a, size_t b) { return (a + b - 1) / b * b; }
