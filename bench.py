@@ -52,6 +52,10 @@ def parse():
     ap.add_argument("--small-group-rows", type=int, default=-1,
                     help="override the mean group size below which the bf16 attention calls use their small-group "
                          "kernels (0: never; default -1: the library's own thresholds)")
+    ap.add_argument("--values", default="random", choices=["random", "zeros"],
+                    help="diagnostic: 'zeros' clears Q, K, V and dO after they are drawn (X, hence the routing and the "
+                         "group sizes, stay): the same instruction stream with minimal switching activity, which shows "
+                         "how far the chip's power limit, and not the kernels' schedule, bounds the run")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-measured-peaks", action="store_true",
                     help="skip the two peak microbenchmarks (register-resident MFMA loop, plain 1 GiB copy)")
@@ -259,6 +263,11 @@ def main():
     inp = wl.make_inputs(w, "cuda")
     X, W, Q, K, V = inp["X"], inp["W"], inp["Q"], inp["K"], inp["V"]
     dO = inp.get("dO")
+    if args.values == "zeros":
+        for t in (Q, K, V, dO):
+            if t is not None:
+                t.zero_()
+        args.no_cpu_baseline = True
     torch.cuda.synchronize()
 
     names = ["moga_route", "moga_permute", "moga_group_attn_fwd", "moga_unpermute"]
@@ -398,7 +407,7 @@ def main():
                   + ("fwd+bwd" if w.backward else "fwd") + "); ms/layer in ms_per_step",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic" + (" (Q, K, V, dO cleared: power diagnostic)" if args.values == "zeros" else ""),
         "config": {"workload": f"{w.name}: N={w.N} ({w.grid} latent grid), H={w.H}, D={w.D}, "
                                f"d_model={w.d_model}, M={w.M}, {w.hidden} hidden states, "
                                + ("forward+backward" if w.backward else "forward")

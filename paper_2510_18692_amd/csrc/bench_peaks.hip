@@ -9,7 +9,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-namespace {
+namespace moga_bench {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float floatx2_t __attribute__((ext_vector_type(2)));
@@ -76,7 +76,9 @@ __global__ __launch_bounds__(256) void copy_kernel(uintx4_t* __restrict__ dst, c
   }
 }
 
-}  // namespace
+}  // namespace moga_bench
+
+using namespace moga_bench;
 
 // Launches `blocks` blocks of 4 waves, each wave issuing iters * 8 MFMAs; returns the FLOPs of the
 // launch (2 * 32 * 32 * 16 per MFMA) or -1 on a bad argument / failed launch.  sink: device, >= blocks * 256 floats.

@@ -94,8 +94,8 @@ def write_layer(args):
     F, W = read_counters(args.fetch), read_counters(args.write)
     line = _bench_line(args.bench_log)
     wl = args.workload
-    cal_f = [v for k, d in F.items() if "copy_kernel" in k for v in d["FETCH_SIZE"]]
-    cal_w = [v for k, d in W.items() if "copy_kernel" in k for v in d["WRITE_SIZE"]]
+    cal_f = [v for k, d in F.items() if "moga_bench::copy_kernel" in k for v in d["FETCH_SIZE"]]
+    cal_w = [v for k, d in W.items() if "moga_bench::copy_kernel" in k for v in d["WRITE_SIZE"]]
     gib_kib = float(1 << 20)
     ff = gib_kib / cal_f[0] if cal_f else 2.0
     fw = gib_kib / cal_w[0] if cal_w else 1.0
@@ -119,7 +119,7 @@ def write_layer(args):
         rate = f"{b / ms / 1e6:.0f} GB/s over {ms:.2f} ms" if ms else "-"
         ctab.append(f"| {c} | {b / 1e9:.2f} GB | {rate} |")
     cmd = ("rocprofv3 --pmc {c} --kernel-trace -d gpurun_out/pmc_{n} -o {n} --output-format csv -- "
-           f"python3 bench.py --workload {wl} --steps 1 --warmup 0 --no-cpu-baseline --calibrate-copy")
+           f"python3 bench.py --workload {wl} --steps 1 --warmup 0 --no-cpu-baseline --no-measured-peaks --calibrate-copy")
     txt = f"""# HBM traffic per kernel launch (rocprofv3 PMC), workload {wl}
 
 Commands (one counter per run, from the repository root on one MI355X):
@@ -156,7 +156,7 @@ Command (run from the repository root on one MI355X):
 
     rocprofv3 --kernel-trace --stats -d gpurun_out/prof_{wl} -o {wl} --output-format csv -- python3 bench.py --workload {wl} --steps {line.get('steps')} --warmup {line.get('warmup')} --no-cpu-baseline
 
-{steps} launches of every kernel per step count.  Library kernels only (torch's input-generation kernels omitted):
+{steps} launches of every kernel (warm-up and timed steps).  Library kernels only (torch's input-generation kernels omitted):
 
 | kernel | calls | avg ms | total ms | % of GPU time |
 |---|---|---|---|---|
@@ -182,40 +182,131 @@ def write_counters(args):
     want = [k for k in merged if any(s in k for s in ("attn_fwd_bf16", "attn_bwd_dkdv", "attn_bwd_dq", "route_mfma",
                                                       "route_bwd_dw_mfma"))]
     names = sorted({c for k in want for c in merged[k]})
-    hdr = "| kernel | " + " | ".join(names) + " |\n|---|" + "---|" * len(names)
-    rows = ["| " + k + " | " + " | ".join(f"{merged[k].get(c, float('nan')):,.0f}" for c in names) + " |" for k in want]
+    short = [k.replace("moga::", "").split("<")[0] for k in want]
+    hdr = "| counter | " + " | ".join(short) + " |\n|---|" + "---|" * len(want)
+    rows = ["| " + c + " | " + " | ".join(f"{merged[k].get(c, float('nan')):,.0f}" for k in want) + " |" for c in names]
     derived = []
     for k in want:
         m = merged[k]
-        parts = [k + ":"]
-        if "SQ_BUSY_CU_CYCLES" in m and "SQ_VALU_MFMA_BUSY_CYCLES" in m and m["SQ_BUSY_CU_CYCLES"] > 0:
-            parts.append(f"MFMA busy / CU busy = {m['SQ_VALU_MFMA_BUSY_CYCLES'] / m['SQ_BUSY_CU_CYCLES']:.3f}")
-        if "GRBM_GUI_ACTIVE" in m and k in stats:
-            parts.append(f"clock = GRBM_GUI_ACTIVE / kernel time = {m['GRBM_GUI_ACTIVE'] / (stats[k]['avg_ms'] * 1e-3) / 1e9:.2f} GHz")
+        parts = []
+        cu_cycles = m.get("SQ_BUSY_CU_CYCLES", 0) / 256.0            # the counter sums the 256 CUs
+        if cu_cycles and "SQ_VALU_MFMA_BUSY_CYCLES" in m:            # summed over the 1024 SIMDs
+            parts.append(f"MFMA busy = SQ_VALU_MFMA_BUSY_CYCLES / (4 x SQ_BUSY_CU_CYCLES) = {m['SQ_VALU_MFMA_BUSY_CYCLES'] / 1024 / cu_cycles:.3f} of the SIMD cycles")
+        if "GRBM_GUI_ACTIVE" in m and k in stats:                     # summed over the 8 XCDs
+            parts.append(f"sustained clock = GRBM_GUI_ACTIVE / 8 / kernel time = {m['GRBM_GUI_ACTIVE'] / 8 / (stats[k]['avg_ms'] * 1e-3) / 1e9:.2f} GHz")
         if "SQ_INSTS_VALU_MFMA_MOPS_BF16" in m and k in stats:
             tf = m["SQ_INSTS_VALU_MFMA_MOPS_BF16"] * 512 / (stats[k]["avg_ms"] * 1e-3) / 1e12
             parts.append(f"executed MFMA rate = MOPS x 512 FLOP / kernel time = {tf:.0f} TFLOP/s ({tf / 2500:.3f} of the published peak)")
-        if "SQ_WAVE_CYCLES" in m and "SQ_WAIT_INST_LDS" in m and m["SQ_WAVE_CYCLES"] > 0:
-            parts.append(f"waiting for LDS = {m['SQ_WAIT_INST_LDS'] / m['SQ_WAVE_CYCLES']:.3f} of wave cycles")
-        if "SQ_LDS_BANK_CONFLICT" in m and "SQ_LDS_IDX_ACTIVE" in m and m["SQ_LDS_IDX_ACTIVE"] > 0:
-            parts.append(f"LDS bank-conflict cycles / LDS active cycles = {m['SQ_LDS_BANK_CONFLICT'] / m['SQ_LDS_IDX_ACTIVE']:.4f}")
-        derived.append("- " + " ".join(parts))
+        if cu_cycles and "SQ_ACTIVE_INST_VALU" in m:                  # in units of 4 cycles, summed over SIMDs
+            parts.append(f"vector ALU active = 4 x SQ_ACTIVE_INST_VALU / SIMD cycles = {4 * m['SQ_ACTIVE_INST_VALU'] / 1024 / cu_cycles:.3f}")
+        if m.get("SQ_WAVE_CYCLES") and "SQ_WAIT_INST_LDS" in m:
+            parts.append(f"waves waiting for LDS = {m['SQ_WAIT_INST_LDS'] / m['SQ_WAVE_CYCLES']:.3f} of wave cycles, for anything = {m.get('SQ_WAIT_INST_ANY', float('nan')) / m['SQ_WAVE_CYCLES']:.3f}")
+        if cu_cycles and "SQ_LDS_IDX_ACTIVE" in m:
+            parts.append(f"LDS active = SQ_LDS_IDX_ACTIVE / CU cycles = {m['SQ_LDS_IDX_ACTIVE'] / 256 / cu_cycles:.3f}, bank conflicts {m.get('SQ_LDS_BANK_CONFLICT', 0):,.0f} cycles")
+        if m.get("SQ_INSTS_MFMA"):
+            parts.append(f"per MFMA: {(m.get('SQ_INSTS_VALU', 0) - m['SQ_INSTS_MFMA']) / m['SQ_INSTS_MFMA']:.2f} other vector instructions, {m.get('SQ_INSTS_LDS', 0) / m['SQ_INSTS_MFMA']:.2f} LDS instructions")
+        derived.append("- **" + k + "**: " + "; ".join(parts))
+    sets = "\n".join(f"    set {i + 1} ({os.path.basename(os.path.dirname(p))}): " + " ".join(sorted(
+        {c for d in read_counters(p).values() for c in d})) for i, p in enumerate(args.csv))
     txt = f"""# MFMA and LDS counters of the matrix-core kernels (rocprofv3 PMC), workload {args.workload}
 
 Commands (one run per counter set, each `timeout -s KILL 300 rocprofv3 --pmc <set> --kernel-trace -d gpurun_out/<dir>
--o <name> --output-format csv -- python3 bench.py --workload {args.workload} --steps 1 --warmup 0 --no-cpu-baseline`):
+-o <name> --output-format csv -- python3 bench.py --workload {args.workload} --steps 1 --warmup 0 --no-cpu-baseline
+--no-measured-peaks`):
 
-""" + "\n".join(f"    set {i + 1}: {os.path.basename(os.path.dirname(p))}: " + " ".join(sorted(
-        {c for d in read_counters(p).values() for c in d})) for i, p in enumerate(args.csv)) + f"""
+{sets}
 
     python -m paper_2510_18692_amd.profiling counters --workload {args.workload} ...   (writes this file)
 
 Kernel times come from the `--kernel-trace --stats` run summarised in layer_{args.workload}_kernel_stats.md.
-Counter values are per dispatch (mean over the dispatches of the run), summed over all XCDs / shader engines as
-rocprofv3 reports them.
+Counter values are per dispatch, summed over the chip as rocprofv3 reports them (256 CUs, 1024 SIMDs, 8 XCDs).
 
 {hdr}
 """ + "\n".join(rows) + "\n\nDerived:\n\n" + "\n".join(derived) + "\n"
+    open(args.out, "w").write(txt)
+    print(txt)
+
+
+def write_block(args):
+    stats = read_kernel_stats(args.stats)
+    line = _bench_line(args.bench_log)
+    rows = list(csv.DictReader(open(args.trace)))
+    rows.sort(key=lambda r: int(r["Dispatch_Id"]))
+    att = [(short_name(r["Kernel_Name"]), (int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e6)
+           for r in rows if "moga::attn_" in r["Kernel_Name"] and "delta" not in r["Kernel_Name"]]
+    per_pass = len(att) // max(1, line.get("steps", 1) + line.get("warmup", 0))
+    last = att[-per_pass:]
+    krows = [f"| {k} | {v['calls']} | {v['avg_ms']:.3f} | {v['total_ms']:.2f} | {v['pct']:.3f} |"
+             for k, v in sorted(stats.items(), key=lambda kv: -kv[1]["total_ms"]) if "moga::" in k]
+    txt = f"""# rocprofv3 kernel stats: three-branch attention block (MoGA + spatial-temporal groups + per-frame groups), fwd+bwd
+
+{line['config']['workload']}; (query, key) pairs {line['config']['pairs']}
+
+Command (run from the repository root on one MI355X):
+
+    rocprofv3 --kernel-trace --stats -d gpurun_out/prof_block -o blk --output-format csv -- python3 bench.py --block --steps {line.get('steps')} --warmup {line.get('warmup')}
+    python -m paper_2510_18692_amd.profiling block ...   (writes this file)
+
+| kernel | calls | avg ms | total ms | % of GPU time |
+|---|---|---|---|---|
+""" + "\n".join(krows) + f"""
+
+bench.py line of the same run: {line['ms_per_step']} ms per pass, {line['value']} effective TFLOP/s over all three branches.
+
+Attention kernels of the last pass in launch order (forward: MoGA, spatial-temporal, per-frame; then the backward
+of each branch, dK/dV before dQ), ms:
+
+""" + "\n".join(f"- {k}: {ms:.2f}" for k, ms in last) + "\n"
+    open(args.out, "w").write(txt)
+    print(txt)
+
+
+def _per_kernel(counter_csv, trace_csv):
+    """{kernel: dict(ms, clock_ghz, mfma_busy)} of one PMC run (GRBM_GUI_ACTIVE, SQ_BUSY_CU_CYCLES, SQ_VALU_MFMA_BUSY_CYCLES)."""
+    c = read_counters(counter_csv)
+    t = collections.defaultdict(list)
+    for r in csv.DictReader(open(trace_csv)):
+        t[short_name(r["Kernel_Name"])].append((int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e6)
+    out = {}
+    for k, d in c.items():
+        if "moga::attn_" not in k or "delta" in k:
+            continue
+        m = {n: sum(v) / len(v) for n, v in d.items()}
+        ms = sum(t[k]) / len(t[k])
+        cu = m["SQ_BUSY_CU_CYCLES"] / 256.0
+        out[k] = {"ms": ms, "clock": m["GRBM_GUI_ACTIVE"] / 8 / (ms * 1e-3) / 1e9,
+                  "busy": m["SQ_VALU_MFMA_BUSY_CYCLES"] / 1024 / cu}
+    return out
+
+
+def write_power(args):
+    rnd = _per_kernel(args.random[0], args.random[1])
+    zer = _per_kernel(args.zeros[0], args.zeros[1])
+    lr, lz = _bench_line(args.random[2]), _bench_line(args.zeros[2])
+    rows = [f"| {k} | {rnd[k]['ms']:.1f} | {rnd[k]['clock']:.2f} | {rnd[k]['busy']:.3f} | {zer[k]['ms']:.1f} | "
+            f"{zer[k]['clock']:.2f} | {zer[k]['busy']:.3f} | {rnd[k]['ms'] / zer[k]['ms']:.2f} |" for k in rnd if k in zer]
+    pk = lr.get("roofline", {}).get("measured_peak")
+    txt = f"""# The attention kernels run at the chip's power limit: random against all-zero operands, workload {args.workload}
+
+Commands (from the repository root on one MI355X; the second run clears Q, K, V and dO after they are drawn, so
+routing, group sizes, grids and every instruction executed are identical, only the switching activity differs):
+
+    rocprofv3 --pmc GRBM_GUI_ACTIVE SQ_BUSY_CU_CYCLES SQ_VALU_MFMA_BUSY_CYCLES --kernel-trace -d gpurun_out/pmc_rand -o rand --output-format csv -- python3 bench.py --workload {args.workload} --steps 2 --warmup 1 --no-cpu-baseline
+    rocprofv3 --pmc GRBM_GUI_ACTIVE SQ_BUSY_CU_CYCLES SQ_VALU_MFMA_BUSY_CYCLES --kernel-trace -d gpurun_out/pmc_zero -o zero --output-format csv -- python3 bench.py --workload {args.workload} --steps 2 --warmup 1 --values zeros
+    python -m paper_2510_18692_amd.profiling power ...   (writes this file)
+
+| kernel | random: ms | clock GHz | MFMA busy | zeros: ms | clock GHz | MFMA busy | time ratio |
+|---|---|---|---|---|---|---|---|
+""" + "\n".join(rows) + f"""
+
+Whole step: {lr['ms_per_step']} ms ({lr['value']} effective TFLOP/s) on random data, {lz['ms_per_step']} ms ({lz['value']}) on zeros.
+Measured peaks of the random run (register-resident MFMA loop on random operands, plain copy): {json.dumps(pk)}.
+
+MFMA busy (cycles the matrix pipes are occupied / SIMD cycles) is a property of the instruction stream and is the
+same in both runs; what changes is the clock the power management grants.  On random data the kernels are held at
+1.7-2.0 GHz of the 2.4 GHz the chip reaches on zeros, and a loop of nothing but MFMAs on random operands is held
+at the rate reported above: that rate, not 2.5 PFLOP/s, is what bf16 matrix work can reach on this chip.
+"""
     open(args.out, "w").write(txt)
     print(txt)
 
@@ -237,6 +328,18 @@ def main():
     b.add_argument("--csv", nargs="+", required=True)
     b.add_argument("--out", required=True)
     b.set_defaults(fn=write_counters)
+    c = sub.add_parser("block")
+    c.add_argument("--stats", required=True)
+    c.add_argument("--trace", required=True)
+    c.add_argument("--bench-log", required=True)
+    c.add_argument("--out", required=True)
+    c.set_defaults(fn=write_block)
+    e = sub.add_parser("power")
+    e.add_argument("--workload", default="C4b")
+    e.add_argument("--random", nargs=3, required=True, metavar=("COUNTERS_CSV", "TRACE_CSV", "BENCH_LOG"))
+    e.add_argument("--zeros", nargs=3, required=True, metavar=("COUNTERS_CSV", "TRACE_CSV", "BENCH_LOG"))
+    e.add_argument("--out", required=True)
+    e.set_defaults(fn=write_power)
     args = ap.parse_args()
     args.fn(args)
 
