@@ -353,12 +353,15 @@ int moga_balance_loss(const int32_t* group, const float* gate, int64_t N, int M,
  * Gradient of the balancing loss with respect to the gate (frac is piecewise constant in the
  * router weights, so only prob carries a gradient):
  *   d_gate[x] (+)= d_loss * alpha * M * frac[group[x]] / N
- * frac [M] from moga_balance_loss; d_loss is the upstream scalar gradient (host value).  With
- * accumulate != 0 the term is added to d_gate (e.g. the output of moga_unpermute_bwd, before
+ * frac [M] from moga_balance_loss.  The upstream scalar gradient is d_loss (a host value) times
+ * d_loss_device_or_null[0] when that device pointer is given (an autograd caller keeps its
+ * gradient on the device and passes d_loss = 1: no host synchronisation), else d_loss alone.
+ * With accumulate != 0 the term is added to d_gate (e.g. the output of moga_unpermute_bwd, before
  * moga_route_bwd); otherwise d_gate is overwritten.
  */
 int moga_balance_loss_bwd(const int32_t* group, const float* frac, int64_t N, int M, float alpha,
-                          float d_loss, int accumulate, float* d_gate, void* stream);
+                          float d_loss, const float* d_loss_device_or_null, int accumulate,
+                          float* d_gate, void* stream);
 
 #ifdef __cplusplus
 }

@@ -41,7 +41,7 @@ class _MogaAttention(torch.autograd.Function):
                                                   fwd["cu_seqlens"], ctx.scale)
         d_q, d_k, d_v = mg.moga_permute_bwd(d_qh, d_kh, d_vh, fwd["perm"])
         if ctx.alpha is not None and d_loss is not None:
-            mg.moga_balance_loss_bwd(fwd["group"], ctx.frac, ctx.alpha, d_loss=float(d_loss), d_gate=d_gate)
+            mg.moga_balance_loss_bwd(fwd["group"], ctx.frac, ctx.alpha, d_loss=d_loss, d_gate=d_gate)
         d_w, d_x = mg.moga_route_bwd(x, w, fwd["probs"], fwd["group"], fwd["gate"], d_gate, want_dx=ctx.grad_x)
         if d_x is not None:
             d_x = d_x.to(x.dtype)

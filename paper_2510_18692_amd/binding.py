@@ -59,7 +59,7 @@ _SIGNATURES = {
     "moga_merge3_fwd": (_i32, [_vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _vp]),
     "moga_merge3_bwd": (_i32, [_vp, _vp, _i32, _vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp, _vp]),
     "moga_balance_loss": (_i32, [_vp, _vp, _i64, _i32, _f32, _vp, _vp, _vp, _vp, _sz, _vp]),
-    "moga_balance_loss_bwd": (_i32, [_vp, _vp, _i64, _i32, _f32, _f32, _i32, _vp, _vp]),
+    "moga_balance_loss_bwd": (_i32, [_vp, _vp, _i64, _i32, _f32, _f32, _vp, _i32, _vp, _vp]),
 }
 EXPORTS = tuple(_SIGNATURES)
 
@@ -422,12 +422,16 @@ def moga_balance_loss(group, gate, M, alpha, stream=None):
 
 
 def moga_balance_loss_bwd(group, frac, alpha, d_loss=1.0, d_gate=None, stream=None):
-    """Adds d_loss * dL/d gate to `d_gate` (in place) or returns a new tensor when d_gate is None."""
+    """Adds d_loss * dL/d gate to `d_gate` (in place) or returns a new tensor when d_gate is None.
+    `d_loss`: a Python number, or a one-element fp32 device tensor (read by the kernel: no host sync)."""
     N, M = group.shape[0], frac.shape[0]
     accumulate = d_gate is not None
     if d_gate is None:
         d_gate = torch.empty(N, dtype=torch.float32, device=group.device)
-    st = load().moga_balance_loss_bwd(_p(group), _p(frac), N, M, float(alpha), float(d_loss),
+    host, dev = (1.0, d_loss) if isinstance(d_loss, torch.Tensor) else (float(d_loss), None)
+    if dev is not None:
+        dev = dev.reshape(1).to(torch.float32)
+    st = load().moga_balance_loss_bwd(_p(group), _p(frac), N, M, float(alpha), host, _p(dev),
                                       int(accumulate), _p(d_gate), _stream(stream))
     _check("moga_balance_loss_bwd", st)
     return d_gate

@@ -69,9 +69,10 @@ __global__ __launch_bounds__(256) void balance_finalize_kernel(
 
 __global__ __launch_bounds__(256) void balance_bwd_kernel(
     const int32_t* __restrict__ group, const float* __restrict__ frac, int64_t N, int M, float coef,
-    int accumulate, float* __restrict__ d_gate) {
+    const float* __restrict__ d_loss_dev, int accumulate, float* __restrict__ d_gate) {
   const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (t >= N) return;
+  if (d_loss_dev) coef *= d_loss_dev[0];   // upstream gradient kept on the device: no host synchronisation
   const int g = group[t];
   const float v = (g >= 0 && g < M) ? coef * frac[g] : 0.f;
   d_gate[t] = accumulate ? d_gate[t] + v : v;
@@ -109,14 +110,14 @@ extern "C" int moga_balance_loss(const int32_t* group, const float* gate, int64_
 }
 
 extern "C" int moga_balance_loss_bwd(const int32_t* group, const float* frac, int64_t N, int M,
-                                     float alpha, float d_loss, int accumulate, float* d_gate,
-                                     void* stream) {
+                                     float alpha, float d_loss, const float* d_loss_device_or_null,
+                                     int accumulate, float* d_gate, void* stream) {
   if (N < 0 || M < 1) return MOGA_ERR_INVALID_ARG;
   if (M > MOGA_MAX_GROUPS || N >= ((int64_t)1 << 31)) return MOGA_ERR_UNSUPPORTED;
   if (N == 0) return MOGA_OK;
   if (!group || !frac || !d_gate) return MOGA_ERR_INVALID_ARG;
   const float coef = (float)((double)d_loss * (double)alpha * (double)M / (double)N);
   balance_bwd_kernel<<<(unsigned)((N + 255) / 256), 256, 0, (hipStream_t)stream>>>(
-      group, frac, N, M, coef, accumulate, d_gate);
+      group, frac, N, M, coef, d_loss_device_or_null, accumulate, d_gate);
   return launch_status();
 }

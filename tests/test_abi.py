@@ -92,8 +92,8 @@ def test_invalid_arguments_return_status_codes_without_a_gpu():
     assert lib.moga_balance_loss(fake, fake, 64, 8, 0.1, None, fake, fake, fake, 4096, None) == -1
     assert lib.moga_balance_loss(fake, fake, 64, 257, 0.1, fake, fake, fake, fake, 8192, None) == -2
     assert lib.moga_balance_loss(fake, fake, 64, 8, 0.1, fake, fake, fake, fake, 8, None) == -3
-    assert lib.moga_balance_loss_bwd(fake, None, 64, 8, 0.1, 1.0, 0, fake, None) == -1
-    assert lib.moga_balance_loss_bwd(fake, fake, 0, 8, 0.1, 1.0, 0, fake, None) == 0
+    assert lib.moga_balance_loss_bwd(fake, None, 64, 8, 0.1, 1.0, None, 0, fake, None) == -1
+    assert lib.moga_balance_loss_bwd(fake, fake, 0, 8, 0.1, 1.0, None, 0, fake, None) == 0
     assert binding.workspace_bytes(binding.OP_BALANCE_LOSS, 4096, 0, 0, 32, 0, 0) >= 32 * 12
 
 

@@ -77,6 +77,10 @@ def test_balance_loss_gradient_matches_oracle(N, M):
     acc = base.clone().cuda()
     mg.moga_balance_loss_bwd(group.cuda(), frac, ALPHA, d_loss=-2.5, d_gate=acc)
     np.testing.assert_allclose(P.to64(acc), P.to64(base) - 2.5 * ref, rtol=1e-6, atol=1e-9)
+    # the upstream gradient as a device scalar (what an autograd caller holds): same result, no host sync
+    acc2 = base.clone().cuda()
+    mg.moga_balance_loss_bwd(group.cuda(), frac, ALPHA, d_loss=torch.tensor(-2.5, device="cuda"), d_gate=acc2)
+    np.testing.assert_allclose(P.to64(acc2), P.to64(base) - 2.5 * ref, rtol=1e-6, atol=1e-9)
 
 
 def test_router_gradient_of_attention_plus_balancing_loss():
