@@ -249,12 +249,14 @@ __global__ __launch_bounds__(NW * 64, NB == 2 ? 2 : 1) void attn_bwd_dq_pipe_ker
   // tile T lives in ring slot T % 4; at the top of tile T the block waits for it, and refills the
   // slot of tile T-1 (which every wave has left) with tile T+3
   const int nfull = n >> 6;   // tiles whose 64 keys are all inside the group
+  // a wave whose query rows all lie past the end of the group only moves its share of the tiles
+  const bool active = q0 + wave * 32 * QW < ge;
   int T = 0;
 #define MOGA_DQ_TILE(B)                                                                  \
   __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * kAhead));                      \
   __syncthreads();                                                                       \
   pipe_issue<NW, GATHER>(dma, 64 * (T + (B) + 1 + kAhead), ((B) + 1 + kAhead) & (NB - 1)); \
-  dq_tile<QW, false, ((B) & (NB - 1)) * kPipeTileBytes>(ln, 0, qf, dof, lq, dl, dq, c, h, 64);
+  if (active) dq_tile<QW, false, ((B) & (NB - 1)) * kPipeTileBytes>(ln, 0, qf, dof, lq, dl, dq, c, h, 64);
   for (; T + 4 <= nfull; T += 4) {   // four tiles per iteration: every LDS offset is an immediate
     MOGA_DQ_TILE(0)
     MOGA_DQ_TILE(1)
@@ -266,12 +268,12 @@ __global__ __launch_bounds__(NW * 64, NB == 2 ? 2 : 1) void attn_bwd_dq_pipe_ker
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * kAhead));
     __syncthreads();
     pipe_issue<NW, GATHER>(dma, 64 * (T + 1 + kAhead), (T + 1 + kAhead) & (NB - 1));
-    dq_tile<QW, false, 0>(ln, ((unsigned)T & (unsigned)(NB - 1)) * kPipeTileBytes, qf, dof, lq, dl, dq, c, h, 64);
+    if (active) dq_tile<QW, false, 0>(ln, ((unsigned)T & (unsigned)(NB - 1)) * kPipeTileBytes, qf, dof, lq, dl, dq, c, h, 64);
   }
   if (n & 63) {   // last, partial tile: masked keys contribute zero
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * kAhead));
     __syncthreads();
-    dq_tile<QW, true, 0>(ln, ((unsigned)T & (unsigned)(NB - 1)) * kPipeTileBytes, qf, dof, lq, dl, dq, c, h, n - 64 * T);
+    if (active) dq_tile<QW, true, 0>(ln, ((unsigned)T & (unsigned)(NB - 1)) * kPipeTileBytes, qf, dof, lq, dl, dq, c, h, n - 64 * T);
   }
 
   __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // drain the look-ahead loads before the LDS is released
@@ -562,13 +564,16 @@ __global__ __launch_bounds__(NPAIR * 128, NB == 2 ? 2 : 1) void attn_bwd_dkdv_ab
     for (int v = 0; v < 16; ++v) acc[dt][v] = 0.f;
 
   const int nfull = n >> 6;   // tiles whose 64 queries are all inside the group
+  // a pair whose 32 key rows lie past the end of the group (both of its waves) only moves its share of the tiles
+  const bool active = k0 + pair * 32 < ge;
   int T = 0;
 #define MOGA_AB_TILE(B)                                                          \
   __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * kAhead));              \
   __syncthreads();                                                               \
   issue_tile(T + (B) + 1 + kAhead);                                          \
-  ab_tile<false, ((B) & (NB - 1)) * kPipeTileBytes, ((B) & (NB - 1)) * 256>(ln, role, 0, 0, kvf, acc, c, h, 64, flag, T + (B) + 1, \
-                                                  spin_limit, status);
+  if (active)                                                                    \
+    ab_tile<false, ((B) & (NB - 1)) * kPipeTileBytes, ((B) & (NB - 1)) * 256>(ln, role, 0, 0, kvf, acc, c, h, 64, flag, \
+                                                                              T + (B) + 1, spin_limit, status);
   for (; T + 4 <= nfull; T += 4) {   // four tiles per iteration: every LDS offset is an immediate
     MOGA_AB_TILE(0)
     MOGA_AB_TILE(1)
@@ -580,14 +585,16 @@ __global__ __launch_bounds__(NPAIR * 128, NB == 2 ? 2 : 1) void attn_bwd_dkdv_ab
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * kAhead));
     __syncthreads();
     issue_tile(T + 1 + kAhead);
-    ab_tile<false, 0, 0>(ln, role, ((unsigned)T & (unsigned)(NB - 1)) * kPipeTileBytes, ((unsigned)T & (unsigned)(NB - 1)) * 256, kvf, acc, c, h, 64,
-                         flag, T + 1, spin_limit, status);
+    if (active)
+      ab_tile<false, 0, 0>(ln, role, ((unsigned)T & (unsigned)(NB - 1)) * kPipeTileBytes,
+                           ((unsigned)T & (unsigned)(NB - 1)) * 256, kvf, acc, c, h, 64, flag, T + 1, spin_limit, status);
   }
   if (n & 63) {   // last, partial tile: masked queries get P = 0 and contribute nothing
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * kAhead));
     __syncthreads();
-    ab_tile<true, 0, 0>(ln, role, ((unsigned)T & (unsigned)(NB - 1)) * kPipeTileBytes, ((unsigned)T & (unsigned)(NB - 1)) * 256, kvf, acc, c, h,
-                        n - 64 * T, flag, T + 1, spin_limit, status);
+    if (active)
+      ab_tile<true, 0, 0>(ln, role, ((unsigned)T & (unsigned)(NB - 1)) * kPipeTileBytes,
+                          ((unsigned)T & (unsigned)(NB - 1)) * 256, kvf, acc, c, h, n - 64 * T, flag, T + 1, spin_limit, status);
   }
 
   __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // drain the look-ahead loads before the LDS is released

@@ -375,6 +375,35 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_bf16_pipe_kernel(
   // ---- prologue: scores of step 0
   __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * kPipeAhead));
   __syncthreads();
+  if (q0 + wave * 32 * QW >= ge) {
+    // Every query row of this wave lies past the end of the group (last tile of a group): it only moves
+    // its share of the K/V tiles and keeps the barriers of the loops below, one for one, so that no
+    // matrix or vector work is spent on padding.
+    int s = 0;
+    for (; s + 8 <= nfull - 1; s += 8) {
+#pragma unroll
+      for (int B = 0; B < 4; ++B) {
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * (kPipeAhead - 1)));
+        __syncthreads();
+        pipe_issue<NW, GATHER>(dma, 32 * s + 64 * (B + 1 + kPipeAhead), (B + 1 + kPipeAhead) & 3);
+      }
+    }
+    while (s + 2 <= nfull - 1) {
+      __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * (kPipeAhead - 1)));
+      __syncthreads();
+      pipe_issue<NW, GATHER>(dma, 32 * (s + 2) + 64 * kPipeAhead, ((s >> 1) + 1 + kPipeAhead) & 3);
+      s += 2;
+    }
+    for (; s < nsteps; ++s) {
+      if ((s & 1) == 1 && s + 1 < nsteps) {
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * (kPipeAhead - 1)));
+        __syncthreads();
+        pipe_issue<NW, GATHER>(dma, 32 * (s + 1) + 64 * kPipeAhead, (((s >> 1) & 3) + 1 + kPipeAhead) & 3);
+      }
+    }
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+    return;
+  }
   floatx16_t s_a[QW], s_b[QW];   // scores of even / odd steps
   float mx[QW];
   {

@@ -130,6 +130,17 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_small_kernel(
   // prologue: scores of step 0 (tile 0)
   __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * kAhead));
   __syncthreads();
+  if (q0 + wave * 32 >= ge) {
+    // every query row of this wave lies past the end of the group: it only moves its share of the K/V
+    // tiles and keeps the barriers of the loops below, one per step
+    for (int s = 0; s < nsteps; ++s) {
+      __builtin_amdgcn_s_waitcnt(waitcnt_vm(kDmaPerTile * (kAhead - 1)));
+      __syncthreads();
+      small_issue_tile(dma, 32 * (s + 1 + kAhead), (s + 1 + kAhead) & 3);
+    }
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+    return;
+  }
   floatx16_t s_a[QW], s_b[QW];   // scores of even / odd steps
   float mx[QW];
   {
