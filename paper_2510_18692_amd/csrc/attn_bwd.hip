@@ -424,6 +424,7 @@ extern "C" int moga_varlen_attn_bwd(const void* d_oh, const void* qh, const void
   hipStream_t st = (hipStream_t)stream;
   if (Nq == 0) {   // keys without any query: zero gradients
     const int64_t nf = Nk * (int64_t)H * D / (dtype == MOGA_BF16 ? 2 : 1);
+    if ((nf + 255) / 256 >= ((int64_t)1 << 31)) return MOGA_ERR_UNSUPPORTED;   // grid of the fill kernel
     fill_zero_kernel<<<(unsigned)((nf + 255) / 256), 256, 0, st>>>((float*)d_kh, nf);
     fill_zero_kernel<<<(unsigned)((nf + 255) / 256), 256, 0, st>>>((float*)d_vh, nf);
     return launch_status();

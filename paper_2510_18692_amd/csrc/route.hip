@@ -689,6 +689,7 @@ extern "C" int moga_route_bwd(const void* x, int x_dtype, const float* w, const 
   if (N < 0 || d_model < 1 || M < 1) return MOGA_ERR_INVALID_ARG;
   if (x_dtype != MOGA_F32 && x_dtype != MOGA_BF16) return MOGA_ERR_UNSUPPORTED;
   if (M > MOGA_MAX_GROUPS || N >= ((int64_t)1 << 31)) return MOGA_ERR_UNSUPPORTED;
+  if (d_model > (1 << 24)) return MOGA_ERR_UNSUPPORTED;   // keeps every grid size below 2^31 blocks
   if (!d_w) return MOGA_ERR_INVALID_ARG;
   hipStream_t st = (hipStream_t)stream;
   const int64_t md = (int64_t)M * d_model;

@@ -125,3 +125,20 @@ def test_new_entry_points_validate_arguments_without_a_gpu():
     wb = binding.workspace_bytes
     assert wb(binding.OP_VARLEN_ATTN_FWD, 1000, 2, 128, 500, 0, 1) >= 501 * 4
     assert wb(binding.OP_VARLEN_ATTN_BWD, 1000, 2, 128, 500, 0, 1) >= 2 * 1000 * 2 * 4 + 2 * 501 * 4
+
+
+def test_row_count_limit_of_the_bf16_attention_calls():
+    """The bf16 attention kernels address the rows of a group with 32-bit byte offsets: 2^24 rows or more
+    are refused on the host (the fp32 kernels take up to 2^31 - 1)."""
+    lib = binding.load()
+    fake = ctypes.c_void_p(0x1000)
+    big = 1 << 24
+    assert lib.moga_group_attn_fwd(fake, fake, fake, 1, big, 2, 128, fake, 4, 0.1, fake, fake, None, 0, None) == -2
+    assert lib.moga_varlen_attn_fwd(fake, fake, fake, 1, 64, big, 2, 128, fake, fake, 3, 0.1, fake, fake, fake, 64, None) == -2
+    assert lib.moga_fused_attn_fwd(fake, fake, fake, 1, big, 2, 128, fake, fake, fake, 4, 0.1, fake, fake, None) == -2
+    ws = binding.workspace_bytes(binding.OP_ATTN_BWD, big, 2, 128, 4, 0, 1)
+    assert lib.moga_group_attn_bwd(fake, fake, fake, fake, fake, fake, 1, big, 2, 128, fake, 4, 0.1, fake, fake, fake,
+                                   fake, ws, None) == -2
+    # the status word of the backward workspace lies behind the two row-constant arrays
+    assert lib.moga_attn_bwd_status_offset(1000, 2) == 2 * 1000 * 2 * 4
+    assert binding.workspace_bytes(binding.OP_ATTN_BWD, 1000, 2, 128, 4, 0, 1) == 2 * 1000 * 2 * 4 + 16
