@@ -359,15 +359,17 @@ def main():
         del held, graph
     nev = len(names) + 1
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(nev)] for _ in range(args.steps)]
+    from paper_2510_18692_amd import profiling
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    counts = None
-    for s in range(args.steps):
-        out = step(evs[s])
-        counts = out["counts"]
-        del out
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
+    with profiling.BoardPower() as board:   # a thread that reads the board's power sensor every 10 ms
+        t0 = time.perf_counter()
+        counts = None
+        for s in range(args.steps):
+            out = step(evs[s])
+            counts = out["counts"]
+            del out
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
     ms_per_step = elapsed * 1e3 / args.steps
 
     counts = counts.cpu().tolist()
@@ -389,8 +391,9 @@ def main():
     roof["kernel"] = dominant
     roof["ms"] = calls[dominant]["ms"]
     # HBM bytes of that call from the tracked rocprofv3 summary of this workload (null if there is none)
-    from paper_2510_18692_amd import profiling
     roof["traffic"] = profiling.read_call_traffic(w.name).get(dominant)
+    # board power over the timed steps (null where the sensor is not readable): the attention calls run at the cap
+    roof["board_power"] = board.summary()
     if peaks is not None:
         roof["measured_peak"] = peaks
         den = peaks["mfma_bf16_tflops"] if roof["bound"] == "mfma" else peaks["hbm_copy_gbs"]

@@ -8,7 +8,10 @@ Usage (after the rocprofv3 runs named in each summary have written their CSV fil
     python -m paper_2510_18692_amd.profiling counters --workload C4b --stats S_kernel_stats.csv \\
         --csv pass1_counter_collection.csv pass2_counter_collection.csv --out profiles/attn_C4b_mfma_counters.md
 
-No GPU is needed for either; nothing here is imported by the library's hot path.
+    python -m paper_2510_18692_amd.profiling energy --out profiles/mfma_energy_probe.md     (runs on the GPU)
+
+Only `energy` needs a GPU; nothing here is imported by the library's hot path.  `BoardPower` samples the
+board power sensor (hwmon, read-only) for bench.py and for `energy`.
 """
 from __future__ import annotations
 
@@ -16,8 +19,11 @@ import argparse
 import collections
 import csv
 import json
+import glob
 import os
 import re
+import threading
+import time
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -31,6 +37,60 @@ _KERNEL_CALL = [
     ("attn_bwd", "moga_group_attn_bwd"),
     ("route_bwd", "moga_route_bwd"),
 ]
+
+
+class BoardPower:
+    """Samples the GPU board power (hwmon `power1_input`, microwatts, of the first card that has one) from a
+    thread while a `with` block runs.  `summary()` is None where the sensor cannot be read.  The sensor
+    averages over some tens of milliseconds, so the mean skips the first `settle_s` seconds."""
+
+    def __init__(self, period_s=0.01, settle_s=0.15):
+        files = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input"))
+        self.path = files[0] if files else None
+        self.period_s, self.settle_s = period_s, settle_s
+        self.samples = []   # (seconds since start, watts)
+        self._stop = threading.Event()
+        self._thread = None
+
+    def _read(self, path):
+        try:
+            with open(path) as f:
+                return int(f.read().strip()) / 1e6
+        except (OSError, ValueError):
+            return None
+
+    def _run(self):
+        t0 = time.perf_counter()
+        while not self._stop.is_set():
+            w = self._read(self.path)
+            if w is not None:
+                self.samples.append((time.perf_counter() - t0, w))
+            time.sleep(self.period_s)
+
+    def __enter__(self):
+        self.samples = []
+        self._stop.clear()
+        if self.path:
+            self._thread = threading.Thread(target=self._run, daemon=True)
+            self._thread.start()
+        return self
+
+    def __exit__(self, *exc):
+        self._stop.set()
+        if self._thread:
+            self._thread.join()
+        return False
+
+    def cap_w(self):
+        return self._read(os.path.join(os.path.dirname(self.path), "power1_cap")) if self.path else None
+
+    def summary(self):
+        late = [w for t, w in self.samples if t >= self.settle_s] or [w for _, w in self.samples]
+        if not late:
+            return None
+        cap = self.cap_w()
+        return {"mean_w": round(sum(late) / len(late), 1), "max_w": round(max(late), 1), "cap_w": cap,
+                "samples": len(late), "source": "hwmon power1_input, 10 ms period, first 0.15 s skipped"}
 
 
 def short_name(kernel: str) -> str:
@@ -311,6 +371,91 @@ at the rate reported above: that rate, not 2.5 PFLOP/s, is what bf16 matrix work
     print(txt)
 
 
+# (LDS fragment reads, fmas, exp2s) per MFMA: the combinations libmoga_bench.so builds
+_ENERGY_VARIANTS = [(0, 0, 0), (1, 0, 0), (2, 0, 0), (0, 2, 0), (0, 4, 0), (0, 6, 0), (0, 0, 1), (0, 0, 2), (1, 4, 1)]
+
+
+def write_energy(args):
+    """Runs the mixed MFMA loop of libmoga_bench.so at the board's power limit and prices an LDS fragment
+    read, an fma and an exp2 in units of the energy of one MFMA."""
+    import ctypes
+
+    import torch
+
+    from . import build as _build
+    lib = ctypes.CDLL(_build.BENCH_LIB)
+    fn = lib.moga_bench_mix_loop
+    fn.restype = ctypes.c_double
+    fn.argtypes = [ctypes.c_int] * 6 + [ctypes.c_void_p, ctypes.c_void_p]
+    blocks, iters, reps = 256, args.iters, args.reps
+    with BoardPower(settle_s=0.0) as bp:   # before the first launch: the idle board
+        time.sleep(0.3)
+    idle = (bp.summary() or {}).get("mean_w")
+    cap = bp.cap_w()
+    sink = torch.empty(blocks * 512, dtype=torch.float32, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    res = {}
+    for zero in (0, 1):
+        for nl, nf, ne in _ENERGY_VARIANTS:
+            assert fn(nl, nf, ne, blocks, 2000, zero, sink.data_ptr(), st) > 0
+            torch.cuda.synchronize()
+            with BoardPower() as bp:
+                e0.record()
+                flop = sum(fn(nl, nf, ne, blocks, iters, zero, sink.data_ptr(), st) for _ in range(reps))
+                e1.record()
+                torch.cuda.synchronize()
+            sec = e0.elapsed_time(e1) * 1e-3
+            pw = bp.summary()
+            res[(zero, nl, nf, ne)] = {"tflops": flop / sec / 1e12, "sec": sec, "watts": pw["mean_w"] if pw else None,
+                                       "busy_ghz": flop / 32768.0 * 32.0 / 1024.0 / sec / 1e9}
+            print(f"zero={zero} lds={nl} fma={nf} exp={ne}: {res[(zero, nl, nf, ne)]}", flush=True)
+
+    def jpf(r):   # joules per PFLOP of MFMA work
+        return r["watts"] / r["tflops"] * 1e3 if r["watts"] else float("nan")
+
+    rows = []
+    for zero in (0, 1):
+        for nl, nf, ne in _ENERGY_VARIANTS:
+            r = res[(zero, nl, nf, ne)]
+            rows.append(f"| {'zeros' if zero else 'random'} | {nl} | {nf} | {ne} | {r['tflops']:.0f} | {r['busy_ghz']:.2f} | "
+                        f"{r['watts'] if r['watts'] is not None else 'n/a'} | {jpf(r):.0f} |")
+    base = res[(0, 0, 0, 0)]
+
+    def per_unit(key, n):
+        return (jpf(res[key]) - jpf(base)) / n
+
+    lds1 = per_unit((0, 1, 0, 0), 1)
+    fma1 = per_unit((0, 0, 6, 0), 6)
+    exp1 = per_unit((0, 0, 0, 2), 2)
+    txt = f"""# What an MFMA, an LDS fragment read, an fma and an exp2 cost at the board's power limit
+
+Command (from the repository root on one MI355X):
+
+    python -m paper_2510_18692_amd.profiling energy --out profiles/mfma_energy_probe.md
+
+`moga_bench_mix_loop` (libmoga_bench.so): 256 blocks of 8 waves (two per SIMD), {reps} launches of {iters} iterations of
+8 register-resident 32x32x16 bf16 MFMAs per wave; per MFMA the stated number of 1 KB LDS fragment reads (16 bytes per
+lane, conflict-free, the fragment is the A or B operand six MFMAs later), fp32 fmas and exp2s.  Power: hwmon
+`power1_input` sampled every 10 ms during the launches (cap {cap} W, idle {idle} W).  "busy x GHz" = MFMA pipe cycles
+per SIMD per nanosecond (2.4 = every cycle of the top clock).  J/PFLOP = board power / MFMA rate.
+
+| operands | LDS reads / MFMA | fma / MFMA | exp2 / MFMA | MFMA TFLOP/s | busy x GHz | board W | J/PFLOP |
+|---|---|---|---|---|---|---|---|
+""" + "\n".join(rows) + f"""
+
+On random operands every variant sits at the same board power: the power management trades clock for switching
+activity, so the rate is set by the energy per MFMA and its companions.  Differences against the plain loop
+({jpf(base):.0f} J/PFLOP): one 1 KB LDS fragment read per MFMA costs {lds1:.0f} J/PFLOP ({100 * lds1 / jpf(base):.0f} % of an MFMA), one fma
+{fma1:.0f} ({100 * fma1 / jpf(base):.1f} %), one exp2 {exp1:.0f} ({100 * exp1 / jpf(base):.1f} %).  The attention kernels read one 1 KB fragment per MFMA
+(32 rows per wave), evaluate about one exp2 and three to four other vector instructions per MFMA and keep the matrix
+pipes busy 57-69 % of the cycles; the sum of those prices plus the idle power over the longer run time is what separates
+their 1.15-1.3 PFLOP/s of executed MFMA work from the plain loop's rate.
+"""
+    open(args.out, "w").write(txt)
+    print(txt)
+
+
 def main():
     ap = argparse.ArgumentParser()
     sub = ap.add_subparsers(dest="cmd", required=True)
@@ -340,6 +485,11 @@ def main():
     e.add_argument("--zeros", nargs=3, required=True, metavar=("COUNTERS_CSV", "TRACE_CSV", "BENCH_LOG"))
     e.add_argument("--out", required=True)
     e.set_defaults(fn=write_power)
+    g = sub.add_parser("energy")
+    g.add_argument("--iters", type=int, default=400000)
+    g.add_argument("--reps", type=int, default=8)
+    g.add_argument("--out", required=True)
+    g.set_defaults(fn=write_energy)
     args = ap.parse_args()
     args.fn(args)
 
