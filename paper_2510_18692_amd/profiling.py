@@ -339,6 +339,11 @@ def _per_kernel(counter_csv, trace_csv):
     return out
 
 
+def _watts(line):
+    bp = line.get("roofline", {}).get("board_power")
+    return f"{bp['mean_w']:.0f} W mean, {bp['max_w']:.0f} W max (cap {bp['cap_w']:.0f} W)" if bp else "not readable"
+
+
 def write_power(args):
     rnd = _per_kernel(args.random[0], args.random[1])
     zer = _per_kernel(args.zeros[0], args.zeros[1])
@@ -352,7 +357,7 @@ Commands (from the repository root on one MI355X; the second run clears Q, K, V 
 routing, group sizes, grids and every instruction executed are identical, only the switching activity differs):
 
     rocprofv3 --pmc GRBM_GUI_ACTIVE SQ_BUSY_CU_CYCLES SQ_VALU_MFMA_BUSY_CYCLES --kernel-trace -d gpurun_out/pmc_rand -o rand --output-format csv -- python3 bench.py --workload {args.workload} --steps 2 --warmup 1 --no-cpu-baseline
-    rocprofv3 --pmc GRBM_GUI_ACTIVE SQ_BUSY_CU_CYCLES SQ_VALU_MFMA_BUSY_CYCLES --kernel-trace -d gpurun_out/pmc_zero -o zero --output-format csv -- python3 bench.py --workload {args.workload} --steps 2 --warmup 1 --values zeros
+    rocprofv3 --pmc GRBM_GUI_ACTIVE SQ_BUSY_CU_CYCLES SQ_VALU_MFMA_BUSY_CYCLES --kernel-trace -d gpurun_out/pmc_zero -o zero --output-format csv -- python3 bench.py --workload {args.workload} --steps 2 --warmup 1 --values zeros --no-cpu-baseline
     python -m paper_2510_18692_amd.profiling power ...   (writes this file)
 
 | kernel | random: ms | clock GHz | MFMA busy | zeros: ms | clock GHz | MFMA busy | time ratio |
@@ -361,6 +366,7 @@ routing, group sizes, grids and every instruction executed are identical, only t
 
 Whole step: {lr['ms_per_step']} ms ({lr['value']} effective TFLOP/s) on random data, {lz['ms_per_step']} ms ({lz['value']}) on zeros.
 Measured peaks of the random run (register-resident MFMA loop on random operands, plain copy): {json.dumps(pk)}.
+Board power over the timed steps (hwmon sensor, `roofline.board_power` of the two bench lines): random {_watts(lr)}, zeros {_watts(lz)}.
 
 MFMA busy (cycles the matrix pipes are occupied / SIMD cycles) is a property of the instruction stream and is the
 same in both runs; what changes is the clock the power management grants.  On random data the kernels are held at
